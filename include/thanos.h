@@ -1,0 +1,129 @@
+/*
+ * libthanos -- Thanos block-wise post-training pruning of one linear layer on AMD MI355X
+ * (gfx950).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * Notation follows the paper ("Formulation of the problem" and its notation table):
+ *   W  in R^{c x b}   weight matrix, c output rows, b input columns, row-major, ld = b
+ *   X                 calibration input.  The paper writes X in R^{b x a}; here it is held
+ *                     token-major, Xc[t, j], t = token, j = input channel (ld = ldx >= b)
+ *   H  in R^{b x b}   Hessian of the row-wise objective, H ~ X X^T (any positive scale)
+ *   M  in {0,1}^{c x b}, M_ij = 1  <=>  W_ij is removed
+ *   B  block size, p sparsity ratio, n:m = n zeros in every m consecutive weights of a row
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless it says "host".  The caller owns all
+ *     buffers; the library allocates no device memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
+ *     enqueued asynchronously on it; nothing synchronises with the host.
+ *   - The return value covers argument checks and launch errors only.  Numerical failure
+ *     (a non-positive pivot) is reported through the device word `info_dev`, which the
+ *     caller reads after synchronising the stream.
+ *   - Matrices are dense row-major.  Pointers should be 16-byte aligned and b a multiple of
+ *     8 for the vectorised paths; other shapes take slower scalar paths, not an error.
+ */
+#ifndef THANOS_H_
+#define THANOS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  THANOS_OK = 0,
+  THANOS_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, m does not divide B or b, ... */
+  THANOS_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels cover (see each call)  */
+  THANOS_ERR_WORKSPACE = 3,   /* ws_bytes smaller than the matching *_workspace_bytes()         */
+  THANOS_ERR_NOT_SPD = 4,     /* reserved for host-side callers that inspect info_dev           */
+  THANOS_ERR_HIP = 5          /* a HIP launch or runtime call failed                            */
+} thanos_status;
+
+typedef enum { THANOS_F32 = 0, THANOS_F16 = 1, THANOS_BF16 = 2 } thanos_dtype;
+typedef enum { THANOS_UNSTRUCTURED = 0, THANOS_NM = 1 } thanos_mode;
+
+/* Options of the block sweep (host struct, read during the call only). */
+typedef struct {
+  int32_t mode;       /* THANOS_UNSTRUCTURED (Alg. 1) or THANOS_NM (n:m algorithm, App. G.4.4) */
+  double sparsity;    /* p in [0,1): r = floor(p*c*b) weights are removed (Alg. 1, problem
+                         statement eq. (2)); p is read as the decimal it prints as, so 0.6
+                         means 6/10.  Ignored for THANOS_NM.                                  */
+  int32_t n, m;       /* THANOS_NM: n of every m consecutive weights of a row are removed;
+                         0 < n < m <= 16, m divides block_size and b                          */
+  int32_t block_size; /* B: columns pruned per sweep step, 1 <= B <= 128; last block may be
+                         narrower (unstructured only)                                         */
+  float damping;      /* H_d = H + damping * mean(diag H) * I (relative damping, >= 0)        */
+  const uint8_t* mask_in;  /* optional c*b device mask that replaces the selection step
+                              (1 = remove); NULL = select as the paper does                   */
+  const float* factor_in;  /* optional U (b*b) from thanos_factor for this H and damping;
+                              NULL = factor inside the call                                   */
+  const float* xnorm2_in;  /* required with factor_in: xnorm2 (b) from the same call          */
+} thanos_prune_opts;
+
+/*
+ * Hessian accumulation, Alg. 1 step "H <- 2 X X^T" in its d-sample form (App. F.2): a sum of
+ * Gram matrices over chunks of calibration tokens.
+ *
+ *   H[i, j] += alpha * sum_{t < n_tok} Xc[t, i] * Xc[t, j]      for i >= j
+ *
+ * H: b*b fp32, ld = b.  Only the lower triangle including the diagonal is defined on return;
+ *    the strict upper triangle may or may not have been written.  The caller zeroes H before
+ *    the first chunk.  Xc: [n_tok, b] of type xdt, row stride ldx elements, never modified.
+ *    Products are exact (fp16/bf16 inputs) and accumulated in fp32 on the matrix cores.
+ * Errors: INVALID_ARG for NULL pointers, b <= 0, n_tok < 0, ldx < b, unknown xdt.
+ *         n_tok == 0 is a no-op.
+ */
+thanos_status thanos_hessian_accumulate(float* H, int64_t b, const void* Xc, thanos_dtype xdt,
+                                        int64_t n_tok, int64_t ldx, float alpha, void* stream);
+
+/*
+ * Damped factorisation.  Replaces the per-block re-inversion of the residual Hessian of
+ * Alg. 1 ("H <- 2(XX^T)_{j2:b, j2:b}" followed by its inverse, cost O(b^4/B) in App. G.6) by
+ * one factor that contains every one of those inverses:
+ *
+ *   xnorm2[j] = H[j, j]                              (undamped, ~ ||X_j:||^2 of the metric, Sec. 4.2)
+ *   H_d       = H + damping * mean_j(H[j, j]) * I
+ *   U upper triangular with  H_d^{-1} = U^T U, hence
+ *   inv(H_d[j:, j:]) = U[j:, j:]^T U[j:, j:]   for every j.
+ *
+ * Reads the lower triangle of H (b*b, ld = b).  Writes U (b*b fp32, ld = b; strict lower
+ * triangle set to 0) and xnorm2 (b).  U must not alias H.  ws: thanos_factor_workspace_bytes(b)
+ * bytes of scratch.  info_dev: device int32; set to 0, or to k > 0 if the pivot of column k
+ * (1-based; columns are eliminated from the last to the first) was not positive, in which
+ * case U is meaningless.  Arithmetic: fp32 throughout (fp32 matrix-core products).
+ */
+thanos_status thanos_factor(const float* H, int64_t b, float damping, float* U, float* xnorm2,
+                            void* ws, size_t ws_bytes, int32_t* info_dev, void* stream);
+size_t thanos_factor_workspace_bytes(int64_t b);
+
+/*
+ * Column-block sweep: Alg. 1 (unstructured, global residual mask psi_X, Sec. 4.4) or the n:m
+ * algorithm of App. G.4.4 with alpha = 0 (no outlier rows).  For every block of B columns,
+ * left to right: choose the block mask M from the metric |W_ij| * sqrt(xnorm2_j) of the
+ * CURRENT weights, then for every row with q = phi(M_i:) (Sec. 4.5) solve lambda R_hat = u and
+ * apply Delta = -u R_hat^{-1} R to all columns from the block start to b (Sec. 4.1, eqs. (R),
+ * (R_hat), (u), (Delta)), with R the rows q of the inverse of the damped residual Hessian.
+ * Removed weights are written as exact zeros.
+ *
+ * W_in: c*b of type wdt, ld = b, never modified.  H: b*b fp32 lower triangle (ignored when
+ * opts->factor_in is given).  W_out: c*b fp32.  W_out_cast: NULL, or c*b of type wdt receiving
+ * W_out rounded to nearest-even.  mask_out: c*b uint8, 1 = removed.  ws:
+ * thanos_prune_workspace_bytes(c, b, opts) bytes.  info_dev: as in thanos_factor.
+ * Ties in the metric are broken by ascending (row, column).
+ * Errors: INVALID_ARG (NULL, sizes, n/m/B constraints, p outside [0,1)), UNSUPPORTED
+ * (block_size > 128, m > 16), WORKSPACE, HIP.
+ */
+thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                 const float* H, const thanos_prune_opts* opts /* host */,
+                                 float* W_out, void* W_out_cast, uint8_t* mask_out, void* ws,
+                                 size_t ws_bytes, int32_t* info_dev, void* stream);
+size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opts* opts /* host */);
+
+/* Static, NUL-terminated description of a status code (host pointer, never freed). */
+const char* thanos_status_string(thanos_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THANOS_H_ */

@@ -1,0 +1,136 @@
+// C ABI of libthanos: argument checks and orchestration only; all arithmetic is in the kernels.
+#include <cmath>
+
+#include "common.h"
+
+namespace thanos {
+size_t factor_workspace_bytes(int64_t b);
+thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
+                     float* xnorm2, void* ws, int32_t* info);
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B);
+thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                    const float* U, const float* xnorm2, const thanos_prune_opts* o,
+                    long long r_total, float* W, void* W_cast, uint8_t* mask, void* ws,
+                    int32_t* info);
+__global__ void k_zero_info(int32_t* info) { *info = 0; }
+}  // namespace thanos
+
+using namespace thanos;
+
+static bool dtype_ok(int d) { return d == THANOS_F32 || d == THANOS_F16 || d == THANOS_BF16; }
+
+// r = floor(p*c*b) with p read as the short decimal it prints as: a product that lands within
+// 1e-6 below an integer is that integer (0.6 * 10 -> 6, not 5).
+static long long num_to_remove(double p, int64_t c, int64_t b) {
+  const long double x = (long double)p * (long double)c * (long double)b;
+  long long r = (long long)floorl(x);
+  if ((long double)(r + 1) - x < 1e-6L) r += 1;
+  return r;
+}
+
+static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b) {
+  if (!o) return THANOS_ERR_INVALID_ARG;
+  if (o->mode != THANOS_UNSTRUCTURED && o->mode != THANOS_NM) return THANOS_ERR_INVALID_ARG;
+  if (o->block_size < 1) return THANOS_ERR_INVALID_ARG;
+  if (!(o->damping >= 0.f)) return THANOS_ERR_INVALID_ARG;
+  if (o->mode == THANOS_UNSTRUCTURED) {
+    if (!(o->sparsity >= 0.0 && o->sparsity < 1.0)) return THANOS_ERR_INVALID_ARG;
+  } else {
+    if (o->n <= 0 || o->m <= o->n) return THANOS_ERR_INVALID_ARG;
+    if (o->block_size % o->m != 0 || b % o->m != 0) return THANOS_ERR_INVALID_ARG;
+    if (o->m > 16) return THANOS_ERR_UNSUPPORTED;
+  }
+  if (o->factor_in && !o->xnorm2_in) return THANOS_ERR_INVALID_ARG;
+  if (o->block_size > 128) return THANOS_ERR_UNSUPPORTED;
+  (void)c;
+  return THANOS_OK;
+}
+
+extern "C" {
+
+const char* thanos_status_string(thanos_status s) {
+  switch (s) {
+    case THANOS_OK: return "ok";
+    case THANOS_ERR_INVALID_ARG: return "invalid argument";
+    case THANOS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case THANOS_ERR_WORKSPACE: return "workspace too small";
+    case THANOS_ERR_NOT_SPD: return "matrix not positive definite";
+    case THANOS_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+thanos_status thanos_hessian_accumulate(float* H, int64_t b, const void* Xc, thanos_dtype xdt,
+                                        int64_t n_tok, int64_t ldx, float alpha, void* stream) {
+  if (!H || b <= 0 || n_tok < 0 || !dtype_ok(xdt)) return THANOS_ERR_INVALID_ARG;
+  if (n_tok == 0) return THANOS_OK;
+  if (!Xc || ldx < b) return THANOS_ERR_INVALID_ARG;
+  if (b > (int64_t)1 << 20) return THANOS_ERR_UNSUPPORTED;
+  return syrk_accumulate(reinterpret_cast<hipStream_t>(stream), H, b, Xc, xdt, n_tok, ldx, alpha);
+}
+
+size_t thanos_factor_workspace_bytes(int64_t b) {
+  if (b <= 0) return 0;
+  return factor_workspace_bytes(b);
+}
+
+thanos_status thanos_factor(const float* H, int64_t b, float damping, float* U, float* xnorm2,
+                            void* ws, size_t ws_bytes, int32_t* info_dev, void* stream) {
+  if (!H || !U || !xnorm2 || !info_dev || b <= 0 || !(damping >= 0.f)) return THANOS_ERR_INVALID_ARG;
+  if (U == H) return THANOS_ERR_INVALID_ARG;
+  if (b > 65535) return THANOS_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < factor_workspace_bytes(b)) return THANOS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
+  return factor(reinterpret_cast<hipStream_t>(stream), H, b, damping, U, xnorm2, ws, info_dev);
+}
+
+size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opts* opts) {
+  if (c <= 0 || b <= 0 || check_opts(opts, c, b) != THANOS_OK) return 0;
+  size_t n = sweep_workspace_bytes(c, b, opts->block_size);
+  if (!opts->factor_in) {
+    n += align_up((size_t)b * b * sizeof(float), 256);  // U
+    n += align_up((size_t)b * sizeof(float), 256);      // xnorm2
+    n += align_up(factor_workspace_bytes(b), 256);
+  }
+  return n;
+}
+
+thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                 const float* H, const thanos_prune_opts* opts, float* W_out,
+                                 void* W_out_cast, uint8_t* mask_out, void* ws, size_t ws_bytes,
+                                 int32_t* info_dev, void* stream) {
+  if (!W_in || !W_out || !mask_out || !info_dev || c <= 0 || b <= 0 || !dtype_ok(wdt))
+    return THANOS_ERR_INVALID_ARG;
+  thanos_status st = check_opts(opts, c, b);
+  if (st != THANOS_OK) return st;
+  if (!opts->factor_in && !H) return THANOS_ERR_INVALID_ARG;
+  if (b > 65535 || c > ((int64_t)1 << 24)) return THANOS_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < thanos_prune_workspace_bytes(c, b, opts)) return THANOS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+  char* p = reinterpret_cast<char*>(ws);
+  void* sweep_ws = p;
+  p += sweep_workspace_bytes(c, b, opts->block_size);
+  const float* U = opts->factor_in;
+  const float* xn2 = opts->xnorm2_in;
+  if (!U) {
+    float* Uw = reinterpret_cast<float*>(p);
+    p += align_up((size_t)b * b * sizeof(float), 256);
+    float* xw = reinterpret_cast<float*>(p);
+    p += align_up((size_t)b * sizeof(float), 256);
+    st = factor(s, H, b, opts->damping, Uw, xw, p, info_dev);
+    if (st != THANOS_OK) return st;
+    U = Uw;
+    xn2 = xw;
+  } else {
+    hipLaunchKernelGGL(k_zero_info, dim3(1), dim3(1), 0, s, info_dev);
+    THANOS_LAUNCH_CHECK();
+  }
+  const long long r_total =
+      (opts->mode == THANOS_UNSTRUCTURED) ? num_to_remove(opts->sparsity, c, b) : 0;
+  return sweep(s, W_in, wdt, c, b, U, xn2, opts, r_total, W_out, W_out_cast, mask_out, sweep_ws,
+               info_dev);
+}
+
+}  // extern "C"

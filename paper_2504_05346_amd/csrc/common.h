@@ -1,0 +1,47 @@
+// Shared host/device helpers of libthanos (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/thanos.h"
+
+#define THANOS_HIP_CHECK(expr)                      \
+  do {                                              \
+    hipError_t e_ = (expr);                         \
+    if (e_ != hipSuccess) return THANOS_ERR_HIP;    \
+  } while (0)
+
+#define THANOS_LAUNCH_CHECK()                                   \
+  do {                                                          \
+    if (hipGetLastError() != hipSuccess) return THANOS_ERR_HIP; \
+  } while (0)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- internal entry points shared between translation units -------------------------------
+namespace thanos {
+
+constexpr int kFactorNB = 128;  // block size of the blocked factorisation
+
+// C[M x N] (ldc) = beta*C + alpha * op(A) * op(B), fp32 on the matrix cores, 128x128 tiles.
+//   a_kmajor: element (m,k) of op(A) is A[k*lda + m], else A[m*lda + k]
+//   b_kmajor: element (k,n) of op(B) is B[k*ldb + n], else B[n*ldb + k]
+//   lower_only: compute only tiles with tile_row >= tile_col (C square)
+thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, int64_t N,
+                       int64_t K, float alpha, const float* A, int64_t lda, const float* B,
+                       int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only);
+
+thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc,
+                              thanos_dtype xdt, int64_t n_tok, int64_t ldx, float alpha);
+
+}  // namespace thanos

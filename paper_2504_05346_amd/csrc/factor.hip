@@ -1,0 +1,259 @@
+// thanos_factor: damping, diagonal extraction and the upper factor U of the inverse of the
+// damped Hessian, H_d^{-1} = U^T U.
+//
+// Why one factor is enough.  Alg. 1 of the paper re-inverts the residual Hessian
+// H_d[j:, j:] after every block (O(b^4/B), App. G.6).  With V upper triangular and
+// H_d = V V^T, the trailing sub-matrix is H_d[j:, j:] = V[j:, j:] V[j:, j:]^T, so with
+// U = V^{-1} (also upper triangular) inv(H_d[j:, j:]) = U[j:, j:]^T U[j:, j:] for every j.
+//
+// How U is computed.  Reversing the index order turns H_d = V V^T into an ordinary Cholesky
+// factorisation: with J the reversal, A' = J H_d J = L L^T (L lower), V = J L J and
+// U = J L^{-1} J.  So: (1) reversed, zero/identity-padded copy A' (ld = bp, a multiple of the
+// factor block NB = 128); (2) right-looking blocked Cholesky: diagonal block in one workgroup
+// (which also produces the inverse of the diagonal block), panel = product with that inverse,
+// trailing update = rank-NB product on the matrix cores; (3) L^{-1} by recursive doubling over
+// block pairs, X21 = -Linv22 * (L21 * Linv11), two products per level; (4) U = J L^{-1} J.
+// Everything is fp32.
+#include "gemm_tile.h"
+
+namespace thanos {
+
+constexpr int NB = kFactorNB;
+
+// ------------------------------------------------------------------------------------------
+// xnorm2[j] = H[j][j];  lam = damping * mean_j H[j][j]  (sum in fp64, fixed order).
+// One workgroup of 1024 threads.
+__global__ __launch_bounds__(1024) void k_diag_stats(const float* __restrict__ H, int64_t b,
+                                                     float damping, float* __restrict__ xnorm2,
+                                                     float* __restrict__ lam_out,
+                                                     int32_t* __restrict__ info) {
+  __shared__ double part[1024];
+  double s = 0.0;
+  for (int64_t j = threadIdx.x; j < b; j += 1024) {
+    const float d = H[j * b + j];
+    xnorm2[j] = d;
+    s += (double)d;
+  }
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = 512; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    *lam_out = (float)((double)damping * (part[0] / (double)b));
+    *info = 0;
+  }
+}
+
+// A'[i][j] = H_d[b-1-i][b-1-j] for i >= j (read from the lower triangle of H as
+// H[b-1-j][b-1-i]); identity on the padding; zero above the diagonal.  32x32 tiles through
+// LDS so that both the read of H and the write of A' are coalesced.
+__global__ __launch_bounds__(256) void k_reverse_pad(const float* __restrict__ H, int64_t b,
+                                                     const float* __restrict__ lam_p,
+                                                     float* __restrict__ Ap, int64_t bp) {
+  __shared__ float t[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int64_t i0 = (int64_t)blockIdx.y * 32, j0 = (int64_t)blockIdx.x * 32;
+  if (j0 > i0 + 31) {  // tile entirely above the diagonal
+    for (int r = ty; r < 32; r += 8) Ap[(i0 + r) * bp + j0 + tx] = 0.f;
+    return;
+  }
+  // A'[i0+r][j0+cidx] = H[b-1-(j0+cidx)][b-1-(i0+r)]: source rows are indexed by cidx,
+  // source columns by r.  Load with lanes along r (source columns, contiguous, descending).
+  for (int cc = ty; cc < 32; cc += 8) {
+    const int64_t sr = b - 1 - (j0 + cc);
+    const int64_t sc = b - 1 - (i0 + tx);
+    float v = 0.f;
+    if (sr >= 0 && sc >= 0 && sr < b && sc < b && sr >= sc) v = H[sr * b + sc];
+    t[cc][tx] = v;  // t[cidx][r]
+  }
+  __syncthreads();
+  const float lam = *lam_p;
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t i = i0 + r, j = j0 + tx;
+    float v;
+    if (j > i) v = 0.f;
+    else if (i >= b) v = (i == j) ? 1.f : 0.f;
+    else v = t[tx][r] + ((i == j) ? lam : 0.f);
+    Ap[i * bp + j] = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Cholesky factor and inverse of one NB x NB diagonal block, one workgroup.
+//   in : lower triangle of A'[kb*NB .. , kb*NB ..]
+//   out: L_kk in the same place (lower triangle), Linv diagonal block = L_kk^{-1} (full
+//        square, zeros above the diagonal).
+// Right-looking elimination; the inverse is built by applying the same column operations to
+// an identity (after step k, row k of T is final and rows > k hold partial sums).
+__global__ __launch_bounds__(256) void k_chol_diag(float* __restrict__ Ap, float* __restrict__ Linv,
+                                                   int64_t bp, int kb, int64_t b,
+                                                   int32_t* __restrict__ info) {
+  __shared__ float S[NB][NB + 1];
+  __shared__ float T[NB][NB + 1];
+  __shared__ float dg[NB];
+  const int tid = threadIdx.x;
+  float* A = Ap + ((int64_t)kb * NB) * bp + (int64_t)kb * NB;
+  float* Li = Linv + ((int64_t)kb * NB) * bp + (int64_t)kb * NB;
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    S[i][j] = (j <= i) ? A[(int64_t)i * bp + j] : 0.f;
+    T[i][j] = (i == j) ? 1.f : 0.f;
+  }
+  const int g = tid >> 5, x = tid & 31;  // 8 row groups x 32 columns
+  for (int k = 0; k < NB; ++k) {
+    __syncthreads();
+    float d = S[k][k];
+    if (!(d > 0.f)) {
+      if (tid == 0) {
+        const int64_t orig = b - ((int64_t)kb * NB + k);  // 1-based original column
+        atomicCAS(info, 0, (int32_t)(orig > 0 ? orig : 1));
+      }
+      d = 1.f;
+    }
+    const float sd = sqrtf(d);
+    const float inv = 1.f / sd;
+    __syncthreads();  // everyone has read S[k][k]
+    if (tid == 0) dg[k] = sd;
+    for (int i = k + 1 + tid; i < NB; i += 256) S[i][k] *= inv;
+    for (int j = tid; j <= k; j += 256) T[k][j] *= inv;
+    __syncthreads();
+    for (int i = k + 1 + g; i < NB; i += 8) {
+      const float lik = S[i][k];
+      for (int j = x; j <= i; j += 32) {
+        if (j <= k) T[i][j] -= lik * T[k][j];
+        else S[i][j] -= lik * S[j][k];
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    if (j < i) A[(int64_t)i * bp + j] = S[i][j];
+    else if (j == i) A[(int64_t)i * bp + j] = dg[i];
+    Li[(int64_t)i * bp + j] = (j <= i) ? T[i][j] : 0.f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Inverse of the block lower-triangular L by recursive doubling.  At level S (in blocks) the
+// matrix is cut into pairs of S-block halves; for each pair
+//     Tbuf21 = L21 * Linv11        (Linv11 lower triangular: k-blocks >= column block)
+//     Linv21 = -Linv22 * Tbuf21    (Linv22 lower triangular: k-blocks <= row block)
+struct TrinvArgs {
+  const float* L;
+  float* Linv;
+  float* T;
+  int64_t bp;
+  int nb, S;
+};
+
+__global__ __launch_bounds__(256) void k_trinv_T(TrinvArgs a) {
+  __shared__ GemmSmem sm;
+  const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
+  const int base = 2 * p * a.S;
+  const int gi = base + a.S + ti, gj = base + tj;
+  if (gi >= a.nb) return;
+  const float* A = a.L + ((int64_t)gi * NB) * a.bp + (int64_t)base * NB;   // [m][k]
+  const float* B = a.Linv + ((int64_t)base * NB) * a.bp + (int64_t)gj * NB;  // [k][n]
+  TileAcc acc;
+  acc_zero(acc);
+  gemm_tile<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, tj * NB, a.S * NB, true, true);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+  float* C = a.T + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB;
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        C[(int64_t)acc_row(wm, f, r, lane) * a.bp + acc_col(wn, g, lane)] = acc.v[f][g][r];
+}
+
+__global__ __launch_bounds__(256) void k_trinv_X(TrinvArgs a) {
+  __shared__ GemmSmem sm;
+  const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
+  const int base = 2 * p * a.S;
+  const int gi = base + a.S + ti, gj = base + tj;
+  if (gi >= a.nb) return;
+  const float* A = a.Linv + ((int64_t)gi * NB) * a.bp + (int64_t)(base + a.S) * NB;  // [m][k]
+  const float* B = a.T + ((int64_t)(base + a.S) * NB) * a.bp + (int64_t)gj * NB;     // [k][n]
+  TileAcc acc;
+  acc_zero(acc);
+  gemm_tile<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, 0, (ti + 1) * NB, true, true);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+  float* C = a.Linv + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB;
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        C[(int64_t)acc_row(wm, f, r, lane) * a.bp + acc_col(wn, g, lane)] = -acc.v[f][g][r];
+}
+
+// U[i][j] = Linv[b-1-i][b-1-j] for j >= i, else 0.
+__global__ __launch_bounds__(256) void k_reverse_out(const float* __restrict__ Linv, int64_t bp,
+                                                     float* __restrict__ U, int64_t b) {
+  const int64_t i = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= b) return;
+  U[i * b + j] = (j >= i) ? Linv[(b - 1 - i) * bp + (b - 1 - j)] : 0.f;
+}
+
+static inline int64_t padded(int64_t b) { return ceil_div(b, NB) * NB; }
+
+size_t factor_workspace_bytes(int64_t b) {
+  const int64_t bp = padded(b);
+  return 3 * (size_t)bp * bp * sizeof(float) + 256;
+}
+
+thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
+                     float* xnorm2, void* ws, int32_t* info) {
+  const int64_t bp = padded(b);
+  const int nb = (int)(bp / NB);
+  float* lam = reinterpret_cast<float*>(ws);
+  float* Ap = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + 256);
+  float* Linv = Ap + bp * bp;
+  float* Tb = Linv + bp * bp;
+
+  hipLaunchKernelGGL(k_diag_stats, dim3(1), dim3(1024), 0, s, H, b, damping, xnorm2, lam, info);
+  THANOS_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_reverse_pad, dim3((unsigned)(bp / 32), (unsigned)(bp / 32)), dim3(256), 0,
+                     s, H, b, lam, Ap, bp);
+  THANOS_LAUNCH_CHECK();
+
+  for (int k = 0; k < nb; ++k) {
+    hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, s, Ap, Linv, bp, k, b, info);
+    THANOS_LAUNCH_CHECK();
+    const int64_t rem = bp - (int64_t)(k + 1) * NB;
+    if (rem <= 0) break;
+    float* panel = Ap + ((int64_t)(k + 1) * NB) * bp + (int64_t)k * NB;
+    const float* dinv = Linv + ((int64_t)k * NB) * bp + (int64_t)k * NB;
+    // L_ik = A_ik * Linv_kk^T  (in place)
+    thanos_status st = gemm_f32(s, false, false, rem, NB, NB, 1.f, panel, bp, dinv, bp, 0.f,
+                                panel, bp, false);
+    if (st != THANOS_OK) return st;
+    // A_ij -= L_ik L_jk^T on the lower tiles of the trailing matrix
+    float* trail = Ap + ((int64_t)(k + 1) * NB) * bp + (int64_t)(k + 1) * NB;
+    st = gemm_f32(s, false, false, rem, rem, NB, -1.f, panel, bp, panel, bp, 1.f, trail, bp, true);
+    if (st != THANOS_OK) return st;
+  }
+
+  for (int S = 1; S < nb; S *= 2) {
+    TrinvArgs a{Ap, Linv, Tb, bp, nb, S};
+    dim3 grid((unsigned)S, (unsigned)S, (unsigned)ceil_div(nb, 2 * S));
+    hipLaunchKernelGGL(k_trinv_T, grid, dim3(256), 0, s, a);
+    THANOS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_trinv_X, grid, dim3(256), 0, s, a);
+    THANOS_LAUNCH_CHECK();
+  }
+
+  hipLaunchKernelGGL(k_reverse_out, dim3((unsigned)ceil_div(b, 256), (unsigned)b), dim3(256), 0, s,
+                     Linv, bp, U, b);
+  THANOS_LAUNCH_CHECK();
+  return THANOS_OK;
+}
+
+}  // namespace thanos

@@ -1,0 +1,71 @@
+// Plain fp32 matrix product on the matrix cores, used by the factorisation and the sweep.
+#include "gemm_tile.h"
+
+namespace thanos {
+
+struct GemmArgs {
+  const float* A;
+  const float* B;
+  float* C;
+  int64_t lda, ldb, ldc;
+  int M, N, K;
+  float alpha, beta;
+  int lower_only;
+  int vec_a, vec_b;
+};
+
+template <bool AK, bool BK>
+__global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs g) {
+  __shared__ GemmSmem sm;
+  const int tn = blockIdx.x, tm = blockIdx.y;
+  if (g.lower_only && tn > tm) return;
+  const int m0 = tm * kTM, n0 = tn * kTN;
+  const int m_ext = min(kTM, g.M - m0), n_ext = min(kTN, g.N - n0);
+  const float* A = AK ? g.A + m0 : g.A + (int64_t)m0 * g.lda;
+  const float* B = BK ? g.B + n0 : g.B + (int64_t)n0 * g.ldb;
+  TileAcc acc;
+  acc_zero(acc);
+  gemm_tile<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, 0, g.K, g.vec_a, g.vec_b);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int gg = 0; gg < 2; ++gg) {
+      const int col = acc_col(wn, gg, lane);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = acc_row(wm, f, r, lane);
+        if (row < m_ext && col < n_ext) {
+          float* p = g.C + (int64_t)(m0 + row) * g.ldc + (n0 + col);
+          const float v = g.alpha * acc.v[f][gg][r];
+          *p = (g.beta == 0.f) ? v : g.beta * (*p) + v;
+        }
+      }
+    }
+}
+
+static inline bool vec_ok(const float* p, int64_t ld) {
+  return (reinterpret_cast<uintptr_t>(p) % 16 == 0) && (ld % 4 == 0);
+}
+
+thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, int64_t N,
+                       int64_t K, float alpha, const float* A, int64_t lda, const float* B,
+                       int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only) {
+  if (M <= 0 || N <= 0) return THANOS_OK;
+  GemmArgs g{A, B, C, lda, ldb, ldc, (int)M, (int)N, (int)K, alpha, beta, lower_only ? 1 : 0,
+             vec_ok(A, lda) ? 1 : 0, vec_ok(B, ldb) ? 1 : 0};
+  dim3 grid((unsigned)ceil_div(N, kTN), (unsigned)ceil_div(M, kTM));
+  if (!a_kmajor && !b_kmajor)
+    hipLaunchKernelGGL((k_gemm_f32<false, false>), grid, dim3(256), 0, s, g);
+  else if (!a_kmajor && b_kmajor)
+    hipLaunchKernelGGL((k_gemm_f32<false, true>), grid, dim3(256), 0, s, g);
+  else if (a_kmajor && b_kmajor)
+    hipLaunchKernelGGL((k_gemm_f32<true, true>), grid, dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL((k_gemm_f32<true, false>), grid, dim3(256), 0, s, g);
+  THANOS_LAUNCH_CHECK();
+  return THANOS_OK;
+}
+
+}  // namespace thanos

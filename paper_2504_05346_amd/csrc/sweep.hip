@@ -1,0 +1,745 @@
+// Column-block sweep of thanos_prune_layer: mask selection, per-row solve, trailing update.
+//
+// Per block [j1, j2) of B columns, with U the factor of thanos_factor (H_d^{-1} = U^T U):
+//   P_k   = U[j1:j2, j1:j2]^T * U[j1:j2, j1:b]      first (j2-j1) rows of inv(H_d[j1:, j1:]),
+//                                                   i.e. every row "R" of Sec. 4.1 can need
+//   G     = P_k[:, 0:j2-j1]                          so that R_hat = G[q, q]
+//   lambda R_hat = u, u = W[i, j1+q]                 per-row solve (eq. (R_hat), (u))
+//   Lam[i, q] = lambda, 0 elsewhere                  scattered multipliers
+//   W[:, j1:b] -= Lam * P_k                          == -u R_hat^{-1} R for every row at once
+// All P_k are produced by one batched launch before the sweep.
+#include <algorithm>
+
+#include "gemm_tile.h"
+
+namespace thanos {
+
+// Orders LDS traffic between the lanes of ONE wavefront (no instruction beyond a wait).
+#define WAVE_SYNC()                                        \
+  do {                                                     \
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); \
+    __builtin_amdgcn_wave_barrier();                       \
+  } while (0)
+
+// ------------------------------------------------------------------------------------------
+// small helpers
+__global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_float(const T* p);
+template <>
+__device__ __forceinline__ float load_as_float<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_as_float<__half>(const __half* p) { return __half2float(*p); }
+template <>
+__device__ __forceinline__ float load_as_float<__hip_bfloat16>(const __hip_bfloat16* p) {
+  return __bfloat162float(*p);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_to_f32(const T* __restrict__ in, float* __restrict__ out,
+                                                int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = load_as_float<T>(in + i);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_from_f32(const float* __restrict__ in, T* __restrict__ out,
+                                                  int64_t n);
+template <>
+__global__ __launch_bounds__(256) void k_from_f32<__half>(const float* __restrict__ in,
+                                                          __half* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = __float2half_rn(in[i]);
+}
+template <>
+__global__ __launch_bounds__(256) void k_from_f32<__hip_bfloat16>(const float* __restrict__ in,
+                                                                  __hip_bfloat16* __restrict__ out,
+                                                                  int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = __float2bfloat16(in[i]);
+}
+template <>
+__global__ __launch_bounds__(256) void k_from_f32<float>(const float* __restrict__ in,
+                                                         float* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}
+
+__global__ __launch_bounds__(256) void k_sqrt(const float* __restrict__ xn2, float* __restrict__ sx,
+                                              int64_t b) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j < b) sx[j] = sqrtf(xn2[j]);
+}
+
+// ------------------------------------------------------------------------------------------
+// P[(j1+m)*b + col] = sum_k U[j1+k][j1+m] * U[j1+k][col], col in [j1, b), for every block.
+struct BlockRowsArgs {
+  const float* U;
+  float* P;
+  int64_t b;
+  int B;
+  int vec;
+};
+
+__global__ __launch_bounds__(256) void k_block_rows(BlockRowsArgs a) {
+  __shared__ GemmSmem sm;
+  const int64_t j1 = (int64_t)blockIdx.y * a.B;
+  const int bw = (int)min((int64_t)a.B, a.b - j1);
+  const int64_t col0 = j1 + (int64_t)blockIdx.x * kTN;
+  if (col0 >= a.b) return;
+  const int n_ext = (int)min((int64_t)kTN, a.b - col0);
+  const float* A = a.U + j1 * a.b + j1;     // (m,k) at A[k*b + m]
+  const float* Bm = a.U + j1 * a.b + col0;  // (k,n) at B[k*b + n]
+  TileAcc acc;
+  acc_zero(acc);
+  gemm_tile<true, true>(acc, sm, A, a.b, bw, Bm, a.b, n_ext, 0, bw, a.vec, a.vec);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int col = acc_col(wn, g, lane);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = acc_row(wm, f, r, lane);
+        if (row < bw && col < n_ext) a.P[(j1 + row) * a.b + col0 + col] = acc.v[f][g][r];
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Unstructured selection: exact r-th smallest metric over the residual W[:, j1:b] by a 3-pass
+// radix select on the fp32 bit pattern (11 + 11 + 10 bits), all state on the device.
+struct SelState {
+  long long r_rem;      // weights still to remove (before the current block)
+  long long rank;       // rank still to resolve inside the current prefix
+  long long need_eq;    // how many keys equal to tau are removed (ties, in (row, col) order)
+  unsigned int prefix;  // resolved high bits
+  unsigned int tau;     // r-th smallest key
+  int blk_count;        // weights removed in the block just finished
+  int none;             // 1: nothing left to remove
+};
+
+__device__ __forceinline__ unsigned int metric_key(float w, float sx) {
+  return __float_as_uint(fabsf(w) * sx);
+}
+
+// One wavefront per row; lanes stride over the residual columns.
+// PASS 0: bin = key >> 21.  PASS 1: keys with key>>21 == prefix, bin = (key>>10) & 2047.
+// PASS 2: keys with key>>10 == prefix, bin = key & 1023; also counts those keys per row.
+template <int PASS>
+__global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, int64_t c, int64_t b,
+                                                  int64_t j1, const float* __restrict__ sx,
+                                                  const SelState* __restrict__ st,
+                                                  unsigned int* __restrict__ hist,
+                                                  int* __restrict__ row_cand) {
+  __shared__ unsigned int h[2048];
+  if (st->none) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int e = tid; e < 2048; e += 256) h[e] = 0u;
+  __syncthreads();
+  const unsigned int prefix = st->prefix;
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+  if (i < c) {
+    const float* row = W + i * b;
+    int cand = 0;
+    for (int64_t j = j1 + lane; j < b; j += 64) {
+      const unsigned int key = metric_key(row[j], sx[j]);
+      if (PASS == 0) {
+        atomicAdd(&h[key >> 21], 1u);
+      } else if (PASS == 1) {
+        if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
+      } else {
+        if ((key >> 10) == prefix) {
+          atomicAdd(&h[key & 1023u], 1u);
+          ++cand;
+        }
+      }
+    }
+    if (PASS == 2) {
+      for (int off = 32; off > 0; off >>= 1) cand += __shfl_down(cand, off, 64);
+      if (lane == 0) row_cand[i] = cand;
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < 2048; e += 256)
+    if (h[e]) atomicAdd(&hist[e], h[e]);
+}
+
+// Single workgroup: locate the bin that contains the wanted rank, fold it into the prefix,
+// clear the histogram for the next pass.
+// Start of a block: r <- r - ||M||_F^2 of the previous block (Alg. 1), reset the search.
+__global__ void k_sel_begin(SelState* __restrict__ st) {
+  st->r_rem -= st->blk_count;
+  st->blk_count = 0;
+  st->rank = st->r_rem;
+  st->prefix = 0u;
+  st->none = (st->r_rem <= 0) ? 1 : 0;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
+                                                  unsigned int* __restrict__ hist) {
+  __shared__ long long part[256];
+  __shared__ int sel_bin;
+  __shared__ long long sel_before;
+  const int tid = threadIdx.x;
+  if (st->none) return;  // the histogram passes did not run either
+  const long long rank = st->rank;
+  unsigned int loc[8];
+  long long s = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    loc[e] = hist[tid * 8 + e];
+    s += loc[e];
+  }
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    long long run = 0;
+    for (int t = 0; t < 256; ++t) {
+      const long long v = part[t];
+      part[t] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  long long before = part[tid];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (before < rank && rank <= before + loc[e]) {
+      sel_bin = tid * 8 + e;
+      sel_before = before;
+    }
+    before += loc[e];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int bits = (PASS == 2) ? 10 : 11;
+    st->prefix = (st->prefix << bits) | (unsigned int)sel_bin;
+    st->rank = rank - sel_before;
+    if (PASS == 2) {
+      st->tau = st->prefix;
+      st->need_eq = st->rank;
+    }
+  }
+  for (int e = tid; e < 2048; e += 256) hist[e] = 0u;
+}
+
+// Ties: rows that hold candidates (keys sharing tau's upper 22 bits) count their keys equal to
+// tau over the residual row; other rows have none.
+__global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, int64_t c, int64_t b,
+                                                  int64_t j1, const float* __restrict__ sx,
+                                                  const SelState* __restrict__ st,
+                                                  const int* __restrict__ row_cand,
+                                                  int* __restrict__ row_eq) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+  if (i >= c) return;
+  if (st->none || row_cand[i] == 0) {
+    if (lane == 0) row_eq[i] = 0;
+    return;
+  }
+  const unsigned int tau = st->tau;
+  const float* row = W + i * b;
+  int n = 0;
+  for (int64_t j = j1 + lane; j < b; j += 64) n += (metric_key(row[j], sx[j]) == tau) ? 1 : 0;
+  for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off, 64);
+  if (lane == 0) row_eq[i] = n;
+}
+
+// Exclusive prefix sum of row_eq over the rows (single workgroup, in place).
+__global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int64_t c) {
+  __shared__ long long part[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (c + 1023) / 1024;
+  const int64_t lo = tid * per, hi = min(c, lo + per);
+  long long s = 0;
+  for (int64_t i = lo; i < hi; ++i) s += row_eq[i];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    long long run = 0;
+    for (int t = 0; t < 1024; ++t) {
+      const long long v = part[t];
+      part[t] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  long long run = part[tid];
+  for (int64_t i = lo; i < hi; ++i) {
+    const int v = row_eq[i];
+    row_eq[i] = (int)min(run, (long long)0x7fffffff);
+    run += v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Mask + per-row solve.  One wavefront per row of W.
+//
+// Solve lambda R_hat = u with R_hat = G[q, q] (symmetric positive definite, s x s, s <= 64*RPL).
+// Lane l owns rows l (and l+64) of R_hat in registers.  Elimination is Gauss-Jordan in its
+// symmetric form: at step k every row rho != k does  A[rho][j] -= l_rho * l_j  with
+// l = A[:, k] / sqrt(A[k][k]), which needs only the pivot COLUMN (each lane's own register)
+// broadcast to all lanes -- done through a small LDS buffer read back as aligned 16-byte
+// vectors.  Registers are indexed by (column - 4*panel): every fourth step writes its results
+// four registers lower, so the pivot columns of a panel are always registers 0..3 and the loop
+// over panels can stay rolled while all register indices are static.  After s steps
+// lambda_k = u_k / A[k][k] (pivot value at step k).
+enum { SEL_NM = 0, SEL_THRESHOLD = 1, SEL_GIVEN = 2 };
+
+struct SolveArgs {
+  const float* W;        // c x b, current weights
+  const float* P;        // b x b, block rows of the residual inverses
+  const float* sx;       // sqrt(xnorm2)
+  const uint8_t* mask_in;
+  uint8_t* mask_out;     // c x b
+  float* Lam;            // c x ldl
+  const SelState* st;    // SEL_THRESHOLD
+  SelState* st_rw;
+  const int* row_eq;     // exclusive tie prefix per row
+  int32_t* info;
+  int64_t c, b, j1;
+  int bw, ldl, n, m;
+};
+
+// CPL = block columns per lane (block width <= 64*CPL), RPL = system rows per lane (s <= 64*RPL).
+template <int CPL, int RPL>
+struct SolveSmem {
+  alignas(16) float col[4][2 * 64 * RPL];  // pivot columns of the current panel; upper half = 0
+  float wrow[64 * CPL];                    // this row's weights of the block, later its lambdas
+  float key[64 * CPL];                     // metric of the block (n:m ranking)
+  int q[64 * CPL];
+};
+
+template <int CPL, int RPL, int SEL, int WPB>
+__global__ __launch_bounds__(64 * WPB) void k_solve(SolveArgs a) {
+  constexpr int SMAX = 64 * RPL;
+  __shared__ SolveSmem<CPL, RPL> smem[WPB];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  SolveSmem<CPL, RPL>& sm = smem[wave];
+  const int64_t i = (int64_t)blockIdx.x * WPB + wave;
+  if (i >= a.c) return;
+  const float* wrow_g = a.W + i * a.b + a.j1;
+
+  // ---- selection of the block mask row M_i ----
+  bool sel[CPL];
+  float wv[CPL];
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const int col = lane + 64 * r;
+    wv[r] = (col < a.bw) ? wrow_g[col] : 0.f;
+    sm.wrow[col] = wv[r];
+    sel[r] = false;
+  }
+  if (SEL == SEL_GIVEN) {
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      sel[r] = (col < a.bw) && a.mask_in[i * a.b + a.j1 + col] != 0;
+    }
+  } else if (SEL == SEL_NM) {
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      sm.key[col] = (col < a.bw) ? fabsf(wv[r]) * a.sx[a.j1 + col] : 0.f;
+    }
+    WAVE_SYNC();
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      if (col < a.bw) {
+        const int g0 = (col / a.m) * a.m;
+        const float mine = sm.key[col];
+        int rank = 0;
+        for (int e = 0; e < a.m; ++e) {
+          const float o = sm.key[g0 + e];
+          rank += (o < mine || (o == mine && g0 + e < col)) ? 1 : 0;
+        }
+        sel[r] = rank < a.n;
+      }
+    }
+  } else {  // SEL_THRESHOLD: key < tau, or key == tau and among the first need_eq ties
+    const bool none = a.st->none != 0;
+    const unsigned int tau = a.st->tau;
+    const long long need_eq = a.st->need_eq;
+    long long tie_rank = a.row_eq[i];
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      const bool in = (col < a.bw) && !none;
+      const unsigned int key = in ? metric_key(wv[r], a.sx[a.j1 + col]) : 0xffffffffu;
+      const bool lt = in && key < tau;
+      const bool eq = in && key == tau;
+      const unsigned long long eqb = __ballot(eq);
+      const long long my = tie_rank + __popcll(eqb & ((1ull << lane) - 1ull));
+      sel[r] = lt || (eq && my < need_eq);
+      tie_rank += __popcll(eqb);
+    }
+  }
+
+  // ---- q = phi(M_i) (ascending column indices) and s ----
+  int s = 0;
+  int myrank[CPL];
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const unsigned long long bal = __ballot(sel[r]);
+    myrank[r] = s + __popcll(bal & ((1ull << lane) - 1ull));
+    s += __popcll(bal);
+  }
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const int col = lane + 64 * r;
+    if (sel[r]) sm.q[myrank[r]] = col;
+    if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[r] ? 1 : 0;
+  }
+  if (SEL == SEL_THRESHOLD) {
+    if (lane == 0 && s > 0) atomicAdd(&a.st_rw->blk_count, s);
+  }
+  float* lam_g = a.Lam + i * a.ldl;
+  if (s == 0 || s > SMAX) {
+    // s > SMAX cannot happen for a launch chosen by the host (it sizes RPL from B, n, m).
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      if (col < a.bw) lam_g[col] = 0.f;
+    }
+    return;
+  }
+  WAVE_SYNC();
+
+  // ---- gather R_hat (by symmetry A[rho][j] = G[q_j][q_rho]: one row of G per load) ----
+  const float* G = a.P + a.j1 * a.b + a.j1;
+  float A[RPL][SMAX];
+  float u[RPL], invd[RPL];
+  int qr[RPL];
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int rho = lane + 64 * r;
+    qr[r] = (rho < s) ? sm.q[rho] : 0;
+    u[r] = (rho < s) ? sm.wrow[qr[r]] : 0.f;
+    invd[r] = 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < SMAX; ++j) {
+    float v[RPL];
+#pragma unroll
+    for (int r = 0; r < RPL; ++r) v[r] = 0.f;
+    if (j < s) {
+      const float* grow = G + (int64_t)sm.q[j] * a.b;
+#pragma unroll
+      for (int r = 0; r < RPL; ++r)
+        if (lane + 64 * r < s) v[r] = grow[qr[r]];
+    }
+#pragma unroll
+    for (int r = 0; r < RPL; ++r) A[r][j] = v[r];
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 2 * RPL; ++r) sm.col[t][lane + 64 * r] = 0.f;
+  WAVE_SYNC();
+
+  // ---- symmetric Gauss-Jordan elimination ----
+  bool bad = false;
+  const int npanel = (s + 3) >> 2;
+  for (int pnl = 0; pnl < npanel; ++pnl) {
+    const int k0 = 4 * pnl;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int k = k0 + t;
+      const int kl = k & 63;
+      float piv = A[0][t], uk = u[0];
+      if (RPL == 2 && k >= 64) {
+        piv = A[RPL - 1][t];
+        uk = u[RPL - 1];
+      }
+      const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(piv), kl));
+      const float ukk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uk), kl));
+      float inv = 0.f;
+      if (k < s) {
+        if (d > 0.f) inv = 1.f / sqrtf(d);
+        else bad = true;
+      }
+      const float yk = ukk * inv;
+      float l[RPL];
+#pragma unroll
+      for (int r = 0; r < RPL; ++r) {
+        const int rho = lane + 64 * r;
+        l[r] = A[r][t] * inv;
+        sm.col[t][rho] = l[r];
+        if (rho == k) {
+          invd[r] = inv;
+          l[r] = 0.f;  // the pivot row itself is not modified
+        }
+        u[r] = fmaf(-l[r], yk, u[r]);
+      }
+      WAVE_SYNC();
+      // pivot column broadcast: register j <-> column k0 + j
+      const f32x4* cb = reinterpret_cast<const f32x4*>(&sm.col[t][k0]);
+      if (t < 3) {
+#pragma unroll
+        for (int j4 = 0; j4 < SMAX / 4; ++j4) {
+          const f32x4 lb = cb[j4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int j = 4 * j4 + e;
+            if (j > t) {
+#pragma unroll
+              for (int r = 0; r < RPL; ++r) A[r][j] = fmaf(-l[r], lb[e], A[r][j]);
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int j4 = 1; j4 < SMAX / 4; ++j4) {
+          const f32x4 lb = cb[j4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int j = 4 * j4 + e;
+#pragma unroll
+            for (int r = 0; r < RPL; ++r) A[r][j - 4] = fmaf(-l[r], lb[e], A[r][j]);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int r = 0; r < RPL; ++r) A[r][SMAX - 4 + e] = 0.f;
+      }
+      WAVE_SYNC();  // reads of col[t] are done before the next panel overwrites it
+    }
+  }
+  if (bad && lane == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
+
+  // ---- lambda row: zeros except lambda_k = u_k / d_k at column q_k ----
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) sm.wrow[lane + 64 * r] = 0.f;
+  WAVE_SYNC();
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int rho = lane + 64 * r;
+    if (rho < s) sm.wrow[qr[r]] = u[r] * invd[r] * invd[r];
+  }
+  WAVE_SYNC();
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const int col = lane + 64 * r;
+    if (col < a.bw) lam_g[col] = sm.wrow[col];
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// W[:, j1:b] -= Lam * P[j1:j2, j1:b]; removed weights of the block become exact zeros.
+struct UpdateArgs {
+  float* W;
+  const float* Lam;
+  const float* P;
+  const uint8_t* mask;
+  int64_t c, b, j1;
+  int bw, ldl, vec_a, vec_b;
+};
+
+__global__ __launch_bounds__(256) void k_update(UpdateArgs a) {
+  __shared__ GemmSmem sm;
+  const int64_t m0 = (int64_t)blockIdx.y * kTM;
+  const int64_t n0 = a.j1 + (int64_t)blockIdx.x * kTN;
+  const int m_ext = (int)min((int64_t)kTM, a.c - m0);
+  const int n_ext = (int)min((int64_t)kTN, a.b - n0);
+  const float* A = a.Lam + m0 * a.ldl;        // (m,k) at A[m*ldl + k]
+  const float* Bm = a.P + a.j1 * a.b + n0;    // (k,n) at B[k*b + n]
+  TileAcc acc;
+  acc_zero(acc);
+  gemm_tile<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.bw, a.vec_a, a.vec_b);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+  const int64_t j2 = a.j1 + a.bw;
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int col = acc_col(wn, g, lane);
+      const int64_t cg = n0 + col;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = acc_row(wm, f, r, lane);
+        if (row < m_ext && col < n_ext) {
+          const int64_t idx = (m0 + row) * a.b + cg;
+          float w = a.W[idx] - acc.v[f][g][r];
+          if (cg < j2 && a.mask[idx]) w = 0.f;
+          a.W[idx] = w;
+        }
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+struct SweepWs {
+  float* sx;
+  float* Lam;
+  float* P;
+  unsigned int* hist;
+  SelState* st;
+  int* row_cand;
+  int* row_eq;
+};
+
+static char* carve(char*& p, size_t bytes) {
+  char* q = p;
+  p += align_up(bytes, 256);
+  return q;
+}
+
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B) {
+  size_t n = 0;
+  n += align_up((size_t)b * 4, 256);            // sx
+  n += align_up((size_t)c * B * 4, 256);        // Lam
+  n += align_up((size_t)b * b * 4, 256);        // P
+  n += align_up(2048 * 4, 256);                 // hist
+  n += align_up(sizeof(SelState), 256);         // state
+  n += 2 * align_up((size_t)c * 4, 256);        // row_cand, row_eq
+  return n;
+}
+
+static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B) {
+  char* p = reinterpret_cast<char*>(ws);
+  SweepWs w;
+  w.sx = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
+  w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * 4));
+  w.P = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
+  w.hist = reinterpret_cast<unsigned int*>(carve(p, 2048 * 4));
+  w.st = reinterpret_cast<SelState*>(carve(p, sizeof(SelState)));
+  w.row_cand = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
+  w.row_eq = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
+  return w;
+}
+
+__global__ void k_init_state(SelState* st, long long r) {
+  st->r_rem = r;
+  st->rank = 0;
+  st->need_eq = 0;
+  st->prefix = 0u;
+  st->tau = 0u;
+  st->blk_count = 0;
+  st->none = (r <= 0) ? 1 : 0;
+}
+
+template <int SEL>
+static void launch_solve(hipStream_t s, const SolveArgs& a, int smax) {
+  // columns per lane from the block width, rows per lane from the largest possible s
+  if (a.bw <= 64) {
+    hipLaunchKernelGGL((k_solve<1, 1, SEL, 4>), dim3((unsigned)ceil_div(a.c, 4)), dim3(256), 0, s, a);
+  } else if (smax <= 64) {
+    hipLaunchKernelGGL((k_solve<2, 1, SEL, 4>), dim3((unsigned)ceil_div(a.c, 4)), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((k_solve<2, 2, SEL, 2>), dim3((unsigned)ceil_div(a.c, 2)), dim3(128), 0, s, a);
+  }
+}
+
+thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                    const float* U, const float* xnorm2, const thanos_prune_opts* o,
+                    long long r_total, float* W, void* W_cast, uint8_t* mask, void* ws,
+                    int32_t* info) {
+  const int B = o->block_size;
+  SweepWs w = carve_ws(ws, c, b, B);
+  const int64_t n = c * b;
+  const unsigned nblk = (unsigned)ceil_div(n, 256);
+
+  if (wdt == THANOS_F32)
+    hipLaunchKernelGGL(k_to_f32<float>, dim3(nblk), dim3(256), 0, s, (const float*)W_in, W, n);
+  else if (wdt == THANOS_F16)
+    hipLaunchKernelGGL(k_to_f32<__half>, dim3(nblk), dim3(256), 0, s, (const __half*)W_in, W, n);
+  else
+    hipLaunchKernelGGL(k_to_f32<__hip_bfloat16>, dim3(nblk), dim3(256), 0, s,
+                       (const __hip_bfloat16*)W_in, W, n);
+  THANOS_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_sqrt, dim3((unsigned)ceil_div(b, 256)), dim3(256), 0, s, xnorm2, w.sx, b);
+  THANOS_LAUNCH_CHECK();
+
+  const bool aligned_b = (b % 4 == 0) && (B % 4 == 0);
+  {
+    BlockRowsArgs a{U, w.P, b, B,
+                    (aligned_b && reinterpret_cast<uintptr_t>(U) % 16 == 0) ? 1 : 0};
+    dim3 grid((unsigned)ceil_div(b, kTN), (unsigned)ceil_div(b, B));
+    hipLaunchKernelGGL(k_block_rows, grid, dim3(256), 0, s, a);
+    THANOS_LAUNCH_CHECK();
+  }
+
+  const bool unstructured = (o->mode == THANOS_UNSTRUCTURED) && o->mask_in == nullptr;
+  if (unstructured) {
+    hipLaunchKernelGGL(k_fill_u32, dim3(8), dim3(256), 0, s, w.hist, (int64_t)2048, 0u);
+    hipLaunchKernelGGL(k_init_state, dim3(1), dim3(1), 0, s, w.st, r_total);
+    THANOS_LAUNCH_CHECK();
+  }
+
+  const unsigned rows4 = (unsigned)ceil_div(c, 4);
+  for (int64_t j1 = 0; j1 < b; j1 += B) {
+    const int bw = (int)std::min<int64_t>(B, b - j1);
+    if (unstructured) {
+      hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(1), 0, s, w.st);
+      hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
+                         w.hist, w.row_cand);
+      hipLaunchKernelGGL(k_sel_scan<0>, dim3(1), dim3(256), 0, s, w.st, w.hist);
+      hipLaunchKernelGGL(k_sel_hist<1>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
+                         w.hist, w.row_cand);
+      hipLaunchKernelGGL(k_sel_scan<1>, dim3(1), dim3(256), 0, s, w.st, w.hist);
+      hipLaunchKernelGGL(k_sel_hist<2>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
+                         w.hist, w.row_cand);
+      hipLaunchKernelGGL(k_sel_scan<2>, dim3(1), dim3(256), 0, s, w.st, w.hist);
+      hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
+                         w.row_cand, w.row_eq);
+      hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c);
+      THANOS_LAUNCH_CHECK();
+    }
+    SolveArgs sa;
+    sa.W = W;
+    sa.P = w.P;
+    sa.sx = w.sx;
+    sa.mask_in = o->mask_in;
+    sa.mask_out = mask;
+    sa.Lam = w.Lam;
+    sa.st = w.st;
+    sa.st_rw = w.st;
+    sa.row_eq = w.row_eq;
+    sa.info = info;
+    sa.c = c;
+    sa.b = b;
+    sa.j1 = j1;
+    sa.bw = bw;
+    sa.ldl = B;
+    sa.n = o->n;
+    sa.m = o->m;
+    if (o->mask_in) {
+      launch_solve<SEL_GIVEN>(s, sa, bw);
+    } else if (o->mode == THANOS_NM) {
+      launch_solve<SEL_NM>(s, sa, bw / o->m * o->n);
+    } else {
+      launch_solve<SEL_THRESHOLD>(s, sa, bw);
+    }
+    THANOS_LAUNCH_CHECK();
+
+    UpdateArgs ua{W, w.Lam, w.P, mask, c, b, j1, bw, B,
+                  (B % 4 == 0) ? 1 : 0,
+                  aligned_b ? 1 : 0};
+    dim3 grid((unsigned)ceil_div(b - j1, kTN), (unsigned)ceil_div(c, kTM));
+    hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
+    THANOS_LAUNCH_CHECK();
+  }
+
+  if (W_cast) {
+    if (wdt == THANOS_F32)
+      hipLaunchKernelGGL(k_from_f32<float>, dim3(nblk), dim3(256), 0, s, W, (float*)W_cast, n);
+    else if (wdt == THANOS_F16)
+      hipLaunchKernelGGL(k_from_f32<__half>, dim3(nblk), dim3(256), 0, s, W, (__half*)W_cast, n);
+    else
+      hipLaunchKernelGGL(k_from_f32<__hip_bfloat16>, dim3(nblk), dim3(256), 0, s, W,
+                         (__hip_bfloat16*)W_cast, n);
+    THANOS_LAUNCH_CHECK();
+  }
+  return THANOS_OK;
+}
+
+}  // namespace thanos

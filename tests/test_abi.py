@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports what include/thanos.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "thanos.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(thanos_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2504_05346_amd as t
+    if not os.path.exists(t.lib_path):
+        from paper_2504_05346_amd import build
+        build.build()
+    return t.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    names = _declared_functions()
+    assert {"thanos_hessian_accumulate", "thanos_factor", "thanos_prune_layer",
+            "thanos_factor_workspace_bytes", "thanos_prune_workspace_bytes",
+            "thanos_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings(L):
+    import paper_2504_05346_amd as t
+    seen = {t.thanos_status_string(s) for s in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert t.thanos_status_string(99) == "unknown status"
+
+
+def test_host_side_argument_checks(L):
+    import paper_2504_05346_amd as t
+    # NULL pointers / bad sizes are rejected before any device work
+    assert L.thanos_hessian_accumulate(None, 8, None, t.THANOS_F16, 4, 8, 1.0, None) == 1
+    assert L.thanos_hessian_accumulate(None, 0, None, t.THANOS_F16, 4, 8, 1.0, None) == 1
+    assert L.thanos_factor(None, 8, 0.01, None, None, None, 0, None, None) == 1
+    o = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=128, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 256, o) > 64 * 128 * 4
+    assert L.thanos_prune_layer(None, t.THANOS_F16, 64, 256, None, ctypes.byref(o), None, None,
+                                None, None, 0, None, None) == 1
+    bad = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=126, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 256, bad) == 0          # m does not divide B
+    big = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=256,
+                      damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 256, big) == 0          # B > 128 unsupported
+    assert t.thanos_factor_workspace_bytes(1000) >= 3 * 1024 * 1024 * 4
+    p1 = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=1.0, n=0, m=0, block_size=128,
+                     damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 256, p1) == 0           # p must be < 1
+
+
+def test_no_oracle_import_in_product():
+    # the product path must never route through the CPU oracle
+    pkg = os.path.join(ROOT, "paper_2504_05346_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("CPU oracle", ""), f

@@ -1,0 +1,223 @@
+"""GPU parity: thanos_prune_layer against the CPU oracle.
+
+Bar: masks bit-exact on inputs without near-ties; W_hat within 1e-3 relative Frobenius error;
+reconstruction error within 1 % of the oracle's.  Both sides receive the same fp32 Hessian, so
+the first block's selection is taken on identical numbers on both sides; later blocks see
+weights that differ by fp32 rounding, which can only flip decisions whose margin is at that
+level (checked through the margins the oracle reports).
+"""
+import numpy as np
+import pytest
+
+from oracle import thanos_oracle as orc
+from synth import LayerSpec, make_weight, make_calibration
+
+pytestmark = pytest.mark.gpu
+
+
+def _layer(c, b, T, dtype="f32", rho=0.7, seed=0, outliers=False):
+    spec = LayerSpec("t", c=c, b=b, tokens=T, dtype=dtype, rho=rho, k_mix=16, seed=seed,
+                     outliers=outliers)
+    W = make_weight(spec)
+    X = make_calibration(spec)
+    H32 = orc.hessian(X).astype(np.float32)
+    return W, H32
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def _check(W, H32, Wg, Mg, Wo, Mo, exact_mask=True):
+    H = H32.astype(np.float64)
+    if exact_mask:
+        np.testing.assert_array_equal(Mg, Mo)
+    assert np.all(Wg[Mg == 1] == 0.0)
+    if np.array_equal(Mg, Mo):
+        assert _rel(Wg, Wo) < 1e-3
+    eo = orc.reconstruction_error(W, Wo, H)
+    eg = orc.reconstruction_error(W, Wg.astype(np.float64), H)
+    assert abs(eg - eo) <= 0.01 * eo + 1e-12
+
+
+# --------------------------------------------------------------------------- configuration 1
+@pytest.mark.parametrize("rho", [0.0, 0.7])
+def test_cfg1_unstructured(rho):
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(512, 512, 2048, "f32", rho=rho, seed=0)
+    print(f"cfg1 unstructured rho={rho}", flush=True)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128)
+    assert info == 0
+    assert int(Mg.sum()) == 512 * 512 // 2
+    Wo, Mo, margins = orc.prune_unstructured(W, H32.astype(np.float64), 0.5, 128, 0.01,
+                                             return_margins=True)
+    assert margins.min() > 1e-6, "seed has a near-tie; pick another"
+    _check(W, H32, Wg, Mg, Wo, Mo)
+    Wm, _ = orc.magnitude_prune(W, p=0.5)
+    H = H32.astype(np.float64)
+    assert orc.reconstruction_error(W, Wg.astype(np.float64), H) <= orc.reconstruction_error(W, Wm, H)
+
+
+@pytest.mark.parametrize("n,m,rho", [(2, 4, 0.0), (2, 4, 0.7), (4, 8, 0.7), (1, 4, 0.7), (3, 4, 0.7)])
+def test_cfg1_nm(n, m, rho):
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(512, 512, 2048, "f32", rho=rho, seed=1)
+    print(f"cfg1 {n}:{m} rho={rho}", flush=True)
+    Wg, Mg, info = gpu_prune(W, H32, mode="nm", n=n, m=m, B=128)
+    assert info == 0
+    assert np.all(Mg.reshape(512, 512 // m, m).sum(axis=2) == n)
+    Wo, Mo, mg = orc.prune_nm(W, H32.astype(np.float64), n, m, 128, 0.01, return_margins=True)
+    bad_rows = np.unique(np.nonzero(Mg != Mo)[0])
+    # a differing group must be a near-tie in the oracle (fp32 vs fp64 weights after updates)
+    if len(bad_rows):
+        gi, gj = np.nonzero((Mg != Mo).reshape(512, 512 // m, m).any(axis=2))
+        first = {}
+        for i, j in zip(gi, gj):
+            first.setdefault(i, j)
+        for i, j in first.items():
+            assert mg[i, j] < 1e-4, (i, j, mg[i, j])
+        assert len(bad_rows) <= 2
+    ok = np.setdiff1d(np.arange(512), bad_rows)
+    np.testing.assert_array_equal(Mg[ok], Mo[ok])
+    assert _rel(Wg[ok], Wo[ok]) < 1e-3
+    _check(W, H32, Wg, Mg, Wo, Mo, exact_mask=False)
+
+
+# --------------------------------------------------------------------------- ragged shapes
+@pytest.mark.parametrize("c,b,B,mode", [
+    (100, 328, 128, "unstructured"),    # c not a multiple of anything, last block 72 wide
+    (100, 328, 128, "nm"),
+    (67, 200, 64, "unstructured"),      # one column per lane
+    (67, 200, 32, "nm"),
+    (130, 260, 100, "unstructured"),    # B not a power of two
+    (50, 150, 50, "unstructured"),      # B and b not multiples of 4: scalar load paths
+    (9, 40, 128, "unstructured"),       # single narrow block
+    (5, 16, 1, "unstructured"),         # B = 1
+])
+def test_ragged_shapes(c, b, B, mode):
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(c, b, 4 * b, "f32", seed=c + b)
+    print(f"ragged c={c} b={b} B={B} {mode}", flush=True)
+    H = H32.astype(np.float64)
+    if mode == "unstructured":
+        Wg, Mg, info = gpu_prune(W, H32, mode=mode, p=0.5, B=B)
+        Wo, Mo = orc.prune_unstructured(W, H, 0.5, B, 0.01)
+        assert int(Mg.sum()) == (c * b) // 2
+    else:
+        Wg, Mg, info = gpu_prune(W, H32, mode=mode, n=2, m=4, B=B)
+        Wo, Mo = orc.prune_nm(W, H, 2, 4, B, 0.01)
+    assert info == 0
+    _check(W, H32, Wg, Mg, Wo, Mo)
+
+
+# --------------------------------------------------------------------------- forced masks
+def test_given_mask_with_empty_and_full_rows():
+    from tests.gpu_util import gpu_prune
+    c, b, B = 96, 384, 128
+    W, H32 = _layer(c, b, 2048, "f32", seed=5)
+    g = np.random.default_rng(0)
+    M = (g.random((c, b)) < g.random((c, 1))).astype(np.uint8)   # per-row density 0..1
+    M[0] = 0
+    M[1] = 1
+    M[2, :128] = 1
+    M[3, 128:256] = 0
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=B, mask_in=M)
+    assert info == 0
+    np.testing.assert_array_equal(Mg, M)
+    Wo, Mo = orc.prune_fast(W, H32.astype(np.float64), mode="unstructured", p=0.5, B=B, damp=0.01,
+                            mask_in=M)
+    assert np.all(Wg[M == 1] == 0.0)
+    np.testing.assert_array_equal(Wg[0], W[0])           # nothing removed: row untouched
+    assert np.all(Wg[1] == 0.0)
+    assert _rel(Wg, Wo) < 1e-3
+    rows = np.linalg.norm(Wg - Wo, axis=1) / np.maximum(np.linalg.norm(Wo, axis=1), 1e-30)
+    assert rows.max() < 1e-3
+
+
+def test_factor_reuse_matches_internal_factor():
+    from tests.gpu_util import gpu_prune, gpu_factor
+    W, H32 = _layer(64, 256, 1024, "f32", seed=6)
+    U, xn2, info = gpu_factor(H32, 0.01)
+    a = gpu_prune(W, H32, mode="nm", n=2, m=4, B=128)
+    b_ = gpu_prune(W, None, mode="nm", n=2, m=4, B=128, U=U, xnorm2=xn2)
+    np.testing.assert_array_equal(a[1], b_[1])
+    np.testing.assert_array_equal(a[0], b_[0])
+
+
+# --------------------------------------------------------------------------- ties
+def test_exact_ties_follow_row_major_order():
+    # Diagonal Hessian: no surviving weight moves, so every block sees heavily tied metrics
+    # (weights from a 5-value set); the mask must equal one global psi with (row, col) ties.
+    from tests.gpu_util import gpu_prune
+    g = np.random.default_rng(1)
+    c, b = 40, 256
+    W = g.choice(np.array([-2.0, -1.0, 0.5, 1.0, 2.0], dtype=np.float32), size=(c, b))
+    H32 = np.diag(g.choice(np.array([1.0, 4.0], dtype=np.float32), size=b))
+    for p in (0.5, 0.3):
+        Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=p, B=64, damp=0.01)
+        assert info == 0
+        Mref = orc.psi(W, np.diag(H32), orc.num_to_remove(p, c, b))
+        np.testing.assert_array_equal(Mg, Mref)
+        np.testing.assert_array_equal(Wg, W * (1 - Mref))
+    Wg, Mg, _ = gpu_prune(W, H32, mode="nm", n=2, m=4, B=64)
+    np.testing.assert_array_equal(Mg, orc.nm_mask(W, np.diag(H32), 2, 4))
+
+
+def test_sparsity_edge_values():
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(16, 128, 512, "f32", seed=7)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.0, B=64)
+    assert Mg.sum() == 0
+    np.testing.assert_array_equal(Wg, W)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.6, B=64)
+    assert int(Mg.sum()) == orc.num_to_remove(0.6, 16, 128)
+    Wo, Mo = orc.prune_unstructured(W, H32.astype(np.float64), 0.6, 64, 0.01)
+    np.testing.assert_array_equal(Mg, Mo)
+
+
+# --------------------------------------------------------------------------- dtypes, determinism
+def test_fp16_weights_cast_output_and_determinism():
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(128, 512, 2048, "f16", seed=8)
+    Wg, Mg, info, Wc = gpu_prune(W, H32, mode="nm", n=2, m=4, B=128, cast=True)
+    assert Wc.dtype == np.float16
+    np.testing.assert_array_equal(Wc, Wg.astype(np.float16))
+    Wo, Mo = orc.prune_nm(W, H32.astype(np.float64), 2, 4, 128, 0.01)
+    ok = np.all(Mg == Mo, axis=1)
+    assert ok.mean() > 0.98
+    assert _rel(Wg[ok], Wo[ok]) < 1e-3
+    W2, M2, _, _ = gpu_prune(W, H32, mode="nm", n=2, m=4, B=128, cast=True)
+    np.testing.assert_array_equal(W2, Wg)
+    np.testing.assert_array_equal(M2, Mg)
+    a = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128)
+    b_ = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128)
+    np.testing.assert_array_equal(a[0], b_[0])
+    np.testing.assert_array_equal(a[1], b_[1])
+
+
+# --------------------------------------------------------------------------- several tiles
+@pytest.mark.parametrize("mode", ["unstructured", "nm"])
+def test_medium_layer_teacher_forced(mode):
+    # 300 x 1024 spans several 128-tiles in both directions and 8 blocks.  The free-running
+    # mask may differ from the float64 oracle at near-ties only; W_hat is compared under the
+    # GPU's own mask (the oracle re-run with that mask forced).
+    from tests.gpu_util import gpu_prune
+    c, b, B = 300, 1024, 128
+    W, H32 = _layer(c, b, 4096, "f16", seed=9)
+    H = H32.astype(np.float64)
+    print(f"medium {mode}", flush=True)
+    if mode == "unstructured":
+        Wg, Mg, info = gpu_prune(W, H32, mode=mode, p=0.5, B=B)
+        Wo, Mo = orc.prune_fast(W, H, mode=mode, p=0.5, B=B, damp=0.01)
+        assert int(Mg.sum()) == c * b // 2
+    else:
+        Wg, Mg, info = gpu_prune(W, H32, mode=mode, n=2, m=4, B=B)
+        Wo, Mo = orc.prune_fast(W, H, mode=mode, n=2, m=4, B=B, damp=0.01)
+        assert np.all(Mg.reshape(c, b // 4, 4).sum(axis=2) == 2)
+    assert info == 0
+    assert (Mg != Mo).mean() < 1e-4
+    Wt, _ = orc.prune_fast(W, H, mode=mode, p=0.5, n=2, m=4, B=B, damp=0.01, mask_in=Mg)
+    assert _rel(Wg, Wt) < 1e-3
+    eo = orc.reconstruction_error(W, Wo, H)
+    eg = orc.reconstruction_error(W, Wg.astype(np.float64), H)
+    assert abs(eg - eo) <= 0.01 * eo
