@@ -44,14 +44,15 @@ def _check(W, H32, Wg, Mg, Wo, Mo, exact_mask=True):
 @pytest.mark.parametrize("rho", [0.0, 0.7])
 def test_cfg1_unstructured(rho):
     from tests.gpu_util import gpu_prune
-    W, H32 = _layer(512, 512, 2048, "f32", rho=rho, seed=0)
+    # seeds searched on the CPU so that the oracle's smallest decision margin is > 5e-6
+    W, H32 = _layer(512, 512, 2048, "f32", rho=rho, seed={0.0: 0, 0.7: 4}[rho])
     print(f"cfg1 unstructured rho={rho}", flush=True)
     Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128)
     assert info == 0
     assert int(Mg.sum()) == 512 * 512 // 2
     Wo, Mo, margins = orc.prune_unstructured(W, H32.astype(np.float64), 0.5, 128, 0.01,
                                              return_margins=True)
-    assert margins.min() > 1e-6, "seed has a near-tie; pick another"
+    assert margins.min() > 5e-6, "seed has a near-tie; pick another"
     _check(W, H32, Wg, Mg, Wo, Mo)
     Wm, _ = orc.magnitude_prune(W, p=0.5)
     H = H32.astype(np.float64)
