@@ -140,7 +140,7 @@ def main():
         e1.record()
         th.thanos_prune_layer(W, H, o, Wo, None, M, ws, info)
         e2.record()
-        if record:
+        if record is not None:
             record.append((e0, e1, e2))
 
     for _ in range(args.warmup):
