@@ -81,58 +81,139 @@ __global__ __launch_bounds__(256) void k_reverse_pad(const float* __restrict__ H
 }
 
 // ------------------------------------------------------------------------------------------
-// Cholesky factor and inverse of one NB x NB diagonal block, one workgroup.
+// Cholesky factor and inverse of one NB x NB diagonal block, one workgroup of 256 threads.
 //   in : lower triangle of A'[kb*NB .. , kb*NB ..]
 //   out: L_kk in the same place (lower triangle), Linv diagonal block = L_kk^{-1} (full
 //        square, zeros above the diagonal).
-// Right-looking elimination; the inverse is built by applying the same column operations to
-// an identity (after step k, row k of T is final and rows > k hold partial sums).
+//
+// In-place elimination on one array X held in REGISTERS, 8x8 elements per thread (thread
+// (bi, bj) owns rows 8bi.., columns 8bj..).  Before step k column j > k of X holds the
+// partially reduced A, afterwards (j <= k) it holds column j of the growing inverse T:
+//   l_i = X[i][k] / sqrt(d),  d = X[k][k]
+//   X[i][j] -= l_i * X[j][k]/sqrt(d)   (j > k: Cholesky update, symmetric source)
+//   X[i][j] -= l_i * X[k][j]/sqrt(d)   (j < k: the same row operation applied to T)
+//   X[i][k]  = -l_i / sqrt(d),  X[k][j<k] /= sqrt(d),  X[k][k] = 1/sqrt(d)
+// for rows i > k only.  Per step the owners of column k and of row k publish 128 values
+// through a double-buffered LDS vector (one barrier per step); everything else is register
+// arithmetic with static indices (the 8 steps of a block column are unrolled).
 __global__ __launch_bounds__(256) void k_chol_diag(float* __restrict__ Ap, float* __restrict__ Linv,
-                                                   int64_t bp, int kb, int64_t b,
+                                                   int64_t bp, int kb_glob, int64_t b,
                                                    int32_t* __restrict__ info) {
-  __shared__ float S[NB][NB + 1];
-  __shared__ float T[NB][NB + 1];
-  __shared__ float dg[NB];
+  __shared__ __attribute__((aligned(16))) float buf[2][NB];
+  __shared__ float Lout[NB][NB + 1];
   const int tid = threadIdx.x;
-  float* A = Ap + ((int64_t)kb * NB) * bp + (int64_t)kb * NB;
-  float* Li = Linv + ((int64_t)kb * NB) * bp + (int64_t)kb * NB;
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
-    S[i][j] = (j <= i) ? A[(int64_t)i * bp + j] : 0.f;
-    T[i][j] = (i == j) ? 1.f : 0.f;
+  const int bi = tid >> 4, bj = tid & 15;
+  float* A = Ap + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
+  float* Li = Linv + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
+  float X[8][8];
+#pragma unroll
+  for (int ii = 0; ii < 8; ++ii) {
+    const float4 a0 = *reinterpret_cast<const float4*>(A + (int64_t)(8 * bi + ii) * bp + 8 * bj);
+    const float4 a1 = *reinterpret_cast<const float4*>(A + (int64_t)(8 * bi + ii) * bp + 8 * bj + 4);
+    X[ii][0] = a0.x; X[ii][1] = a0.y; X[ii][2] = a0.z; X[ii][3] = a0.w;
+    X[ii][4] = a1.x; X[ii][5] = a1.y; X[ii][6] = a1.z; X[ii][7] = a1.w;
   }
-  const int g = tid >> 5, x = tid & 31;  // 8 row groups x 32 columns
-  for (int k = 0; k < NB; ++k) {
-    __syncthreads();
-    float d = S[k][k];
-    if (!(d > 0.f)) {
-      if (tid == 0) {
-        const int64_t orig = b - ((int64_t)kb * NB + k);  // 1-based original column
-        atomicCAS(info, 0, (int32_t)(orig > 0 ? orig : 1));
+  int badk = -1;
+  for (int kb = 0; kb < NB / 8; ++kb) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const int k = 8 * kb + kk;
+      float* bw = buf[k & 1];
+      // publish column k (rows >= k) and row k (columns < k): 8 consecutive entries per owner
+      if (bj == kb && bi == kb) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (e < kk) ? X[kk][e] : X[e][kk];
+        *reinterpret_cast<float4*>(&bw[8 * kb]) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(&bw[8 * kb + 4]) = make_float4(v[4], v[5], v[6], v[7]);
+      } else if (bj == kb && bi > kb) {
+        *reinterpret_cast<float4*>(&bw[8 * bi]) =
+            make_float4(X[0][kk], X[1][kk], X[2][kk], X[3][kk]);
+        *reinterpret_cast<float4*>(&bw[8 * bi + 4]) =
+            make_float4(X[4][kk], X[5][kk], X[6][kk], X[7][kk]);
+      } else if (bi == kb && bj < kb) {
+        *reinterpret_cast<float4*>(&bw[8 * bj]) =
+            make_float4(X[kk][0], X[kk][1], X[kk][2], X[kk][3]);
+        *reinterpret_cast<float4*>(&bw[8 * bj + 4]) =
+            make_float4(X[kk][4], X[kk][5], X[kk][6], X[kk][7]);
       }
-      d = 1.f;
-    }
-    const float sd = sqrtf(d);
-    const float inv = 1.f / sd;
-    __syncthreads();  // everyone has read S[k][k]
-    if (tid == 0) dg[k] = sd;
-    for (int i = k + 1 + tid; i < NB; i += 256) S[i][k] *= inv;
-    for (int j = tid; j <= k; j += 256) T[k][j] *= inv;
-    __syncthreads();
-    for (int i = k + 1 + g; i < NB; i += 8) {
-      const float lik = S[i][k];
-      for (int j = x; j <= i; j += 32) {
-        if (j <= k) T[i][j] -= lik * T[k][j];
-        else S[i][j] -= lik * S[j][k];
+      __syncthreads();
+      float d = bw[k];
+      if (!(d > 0.f)) {
+        if (badk < 0) badk = k;
+        d = 1.f;
+      }
+      const float sd = sqrtf(d);
+      const float inv = 1.f / sd;
+      if (bi >= kb) {  // rows of earlier block rows are final
+        const float4 r0 = *reinterpret_cast<const float4*>(&bw[8 * bi]);
+        const float4 r1 = *reinterpret_cast<const float4*>(&bw[8 * bi + 4]);
+        const float4 c0 = *reinterpret_cast<const float4*>(&bw[8 * bj]);
+        const float4 c1 = *reinterpret_cast<const float4*>(&bw[8 * bj + 4]);
+        float li[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+        float vj[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float s_hi = (bi > kb) ? inv : 0.f;  // rows of this thread with row <= k get 0
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          li[e] *= (e > kk) ? inv : s_hi;
+          vj[e] *= inv;
+        }
+        if (bi == kb) {  // row k becomes final: T[k][j<k] scaled, T[k][k] = 1/sqrt(d)
+          if (bj < kb) {
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) X[kk][jj] = vj[jj];
+          } else if (bj == kb) {
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+              if (jj < kk) X[kk][jj] = vj[jj];
+              else if (jj == kk) X[kk][jj] = inv;
+            }
+          }
+        }
+#pragma unroll
+        for (int ii = 0; ii < 8; ++ii)
+#pragma unroll
+          for (int jj = 0; jj < 8; ++jj) X[ii][jj] = fmaf(-li[ii], vj[jj], X[ii][jj]);
+        if (bj == kb) {  // column k: publish L[:, k], start column k of the inverse
+          if (bi > kb) {
+#pragma unroll
+            for (int ii = 0; ii < 8; ++ii) {
+              Lout[8 * bi + ii][k] = li[ii];
+              X[ii][kk] = -li[ii] * inv;
+            }
+          } else {
+#pragma unroll
+            for (int ii = 0; ii < 8; ++ii) {
+              if (ii > kk) {
+                Lout[8 * bi + ii][k] = li[ii];
+                X[ii][kk] = -li[ii] * inv;
+              } else if (ii == kk) {
+                Lout[8 * bi + ii][k] = sd;
+              }
+            }
+          }
+        }
       }
     }
+  }
+  if (badk >= 0 && tid == 0) {
+    const int64_t orig = b - ((int64_t)kb_glob * NB + badk);  // 1-based original column
+    atomicCAS(info, 0, (int32_t)(orig > 0 ? orig : 1));
   }
   __syncthreads();
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
-    if (j < i) A[(int64_t)i * bp + j] = S[i][j];
-    else if (j == i) A[(int64_t)i * bp + j] = dg[i];
-    Li[(int64_t)i * bp + j] = (j <= i) ? T[i][j] : 0.f;
+    if (j <= i) A[(int64_t)i * bp + j] = Lout[i][j];
+  }
+#pragma unroll
+  for (int ii = 0; ii < 8; ++ii) {
+    const int i = 8 * bi + ii;
+    float o[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) o[jj] = (8 * bj + jj <= i) ? X[ii][jj] : 0.f;
+    float* dst = Li + (int64_t)i * bp + 8 * bj;
+    *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<float4*>(dst + 4) = make_float4(o[4], o[5], o[6], o[7]);
   }
 }
 
