@@ -1,20 +1,29 @@
 // thanos_hessian_accumulate: H += alpha * Xc^T Xc on the CDNA4 matrix cores.
 //
 // Xc is token-major [n_tok, b] (16-bit floats), so both MFMA operands of H = Xc^T Xc are
-// "channel-contiguous": the reduction index (token) is the strided one.  The 16-bit MFMA wants
-// 8 consecutive reduction values per lane in 4 VGPRs, so every 8-token x 8-channel patch is
-// transposed in registers (v_perm_b32) on its way from global memory to LDS.  Two freedoms of a
-// Gram matrix make the LDS traffic conflict-free in both directions:
-//   * the order of the reduction index is arbitrary as long as both operands use the same one;
-//   * a 32-row MFMA operand may be ANY 32 channels: fragment f of a 256-channel panel is
-//     {8x + f : x = 0..31}, which is exactly what 32 lanes hold after the register transpose.
+// "channel-contiguous": the reduction index (token) is the strided one, while the 16-bit MFMA
+// wants 8 consecutive reduction values per lane.
 //
 // Workgroup = 256 threads = 4 wavefronts (2x2), tile = 256 x 256 outputs, each wavefront
-// 128 x 128 = 4x4 MFMA 32x32x16 tiles (256 accumulator registers).  A k-step is 64 tokens:
-// 8 octets of 8 tokens; LDS stage = 8 octets x 512 channel slots x 16 B = 64 KB, two stages.
-// Only tiles on or below the diagonal are computed.  Workgroups are renumbered so that the 32
-// workgroups resident on one XCD work on a 4 x 8 patch of neighbouring tiles and share their
-// panels of X through that XCD's L2.
+// 128 x 128 = 4x4 MFMA 32x32x16 tiles (256 accumulator registers).  Only tiles on or below the
+// diagonal are computed.  Workgroups are renumbered so that the 32 workgroups resident on one
+// XCD work on a 4 x 8 patch of neighbouring tiles and share their panels of X through that
+// XCD's L2.
+//
+// Main kernel (k_syrk16_dma; 16-byte aligned rows, b % 8 == 0):
+//   * global -> LDS without registers: buffer_load_dwordx4 ... lds.  One wavefront-wide load
+//     moves one token row of both panels (2 x 256 channels = 1 KB) into one LDS row; rows past
+//     n_tok are outside the buffer descriptor and arrive as zeros.  Four stages of 32 tokens
+//     (row stride 1088 B) keep three k-steps (96 KB per workgroup) in flight.
+//   * LDS -> MFMA operand with the transposing read ds_read_b64_tr_b16: within 16 lanes, lane
+//     s fetches 8 bytes of row (s / 4), channels 4 (s % 4)..+3, and receives the four rows of
+//     ONE channel, i.e. four consecutive reduction values; two such reads make an operand.
+//     The 64-byte row padding spreads the four rows of a read over all 64 banks.
+//   * one barrier per k-step: wait for the own loads of this step (vmcnt), barrier, issue the
+//     loads three steps ahead into the stage that was consumed last, multiply.
+// Fallback kernel (k_syrk16; any alignment, any b): 8x8 patches are loaded with guarded scalar
+// loads, transposed in registers (v_perm_b32) and written to LDS already k-packed; fragment f
+// of a panel is the channel set {8x + f}, which keeps both LDS directions conflict-free.
 #include "common.h"
 #include "gemm_tile.h"
 
@@ -205,6 +214,162 @@ __global__ __launch_bounds__(256) void k_syrk16(SyrkArgs a) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+constexpr int kDmaKT = 32;                 // tokens per k-step
+constexpr int kDmaStages = 4;
+constexpr int kDmaRow = 1024 + 64;         // bytes per LDS token row (2 x 256 channels + pad)
+constexpr int kDmaStageBytes = kDmaKT * kDmaRow;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 frag_read_tr(const char* lds_lane_base, int byte_off) {
+  // two transposing reads: tokens +0..3 and +4..7 of this lane's channel
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_lane_base + byte_off));
+  const s16x4 hi4 =
+      __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_lane_base + byte_off + 4 * kDmaRow));
+  u32x4 o;
+  o.x = (uint16_t)lo4[0] | ((uint32_t)(uint16_t)lo4[1] << 16);
+  o.y = (uint16_t)lo4[2] | ((uint32_t)(uint16_t)lo4[3] << 16);
+  o.z = (uint16_t)hi4[0] | ((uint32_t)(uint16_t)hi4[1] << 16);
+  o.w = (uint16_t)hi4[2] | ((uint32_t)(uint16_t)hi4[3] << 16);
+  return o;
+}
+
+// One wavefront-wide 16-byte-per-lane load straight into LDS: lane l's 16 bytes land at
+// lds_addr + 16*l.  Written as inline assembly so that the compiler's wait-count insertion does
+// not serialise every LDS read behind all outstanding loads; the kernel waits explicitly.
+__device__ __forceinline__ void dma_row(const u32x4& rsrc, uint32_t lds_addr, uint32_t voff,
+                                        uint32_t soff) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "buffer_load_dwordx4 %1, %2, %3 offen lds"
+      :
+      : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+      : "memory");
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_syrk16_dma(SyrkArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lo = lane & 31, hi = lane >> 5;
+
+  const int nwg = a.ntiles;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int logical = xcd * (nwg >> 3) + min(xcd, nwg & 7) + local;
+  int ti, tj;
+  tile_from_index(logical, a.nt, ti, tj);
+  const int64_t i0 = (int64_t)ti * kSyTile, j0 = (int64_t)tj * kSyTile;
+
+  // producer: lane -> 8 channels of one token row; lanes 0..31 i-panel, 32..63 j-panel
+  const int64_t ch0 = (lane < 32 ? i0 : j0) + 8 * (lane & 31);
+  const uint32_t voff = (uint32_t)(ch0 * 2);
+  const uint32_t lds_base =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+
+  // consumer: byte offset of this lane's transposing read inside a stage, fragment 0, slice 0
+  const int s16 = lane & 15, g16 = (lane & 31) >> 4;
+  const int lane_off = (8 * hi + (s16 >> 2)) * kDmaRow + (16 * g16 + 4 * (s16 & 3)) * 2;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[f][g][r] = 0.f;
+
+  const int64_t nkt = (a.n_tok + kDmaKT - 1) / kDmaKT;
+
+  // Issue the 8 row loads of this wavefront for k-step kt (rows 8*wave .. 8*wave+7 of the
+  // step).  Steps past the end get an empty descriptor: every lane is out of range, nothing is
+  // read and zeros are written, so the wait counts below stay uniform.
+  auto issue = [&](int64_t kt) {
+    const int64_t t0 = kt * kDmaKT + 8 * wave;
+    int64_t rem_bytes = ((a.n_tok - t0 - 1) * a.ldx + a.b) * 2;
+    const uint16_t* base = a.X + t0 * a.ldx;
+    if (t0 >= a.n_tok) {
+      rem_bytes = 0;
+      base = a.X;
+    }
+    const uint32_t nrec = rem_bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)rem_bytes;
+    const uint64_t ba = reinterpret_cast<uint64_t>(base);
+    u32x4 rs;
+    rs.x = __builtin_amdgcn_readfirstlane((uint32_t)ba);
+    rs.y = __builtin_amdgcn_readfirstlane((uint32_t)(ba >> 32) & 0xffffu);  // stride 0
+    rs.z = __builtin_amdgcn_readfirstlane(nrec);
+    rs.w = 0x00020000u;
+    const uint32_t dst = lds_base + (uint32_t)((int)(kt % kDmaStages) * kDmaStageBytes +
+                                               (8 * wave) * kDmaRow);
+    const uint32_t row_bytes = __builtin_amdgcn_readfirstlane((uint32_t)(a.ldx * 2));
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+      dma_row(rs, __builtin_amdgcn_readfirstlane(dst + r * kDmaRow), voff, r * row_bytes);
+  };
+  auto read_frags = [&](int64_t kt, int ks, u32x4 (&af)[4], u32x4 (&bf)[4]) {
+    const char* st = lds + (int)(kt % kDmaStages) * kDmaStageBytes + lane_off + ks * 16 * kDmaRow;
+#pragma unroll
+    for (int f = 0; f < 4; ++f) af[f] = frag_read_tr(st, (32 * (4 * wm + f)) * 2);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) bf[g] = frag_read_tr(st, 512 + (32 * (4 * wn + g)) * 2);
+  };
+  auto mma = [&](const u32x4 (&af)[4], const u32x4 (&bf)[4]) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[f][g] = mfma16<BF16>(af[f], bf[g], acc[f][g]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Schedule per k-step kt (two 16-token slices):
+  //   read slice 1 of kt | MFMA slice 0 of kt | wait: own loads of kt+1 landed, own LDS reads
+  //   done | barrier | issue loads of kt+4 into the stage of kt | read slice 0 of kt+1 |
+  //   MFMA slice 1 of kt.
+  // Every MFMA group has its operands fetched one group earlier, and the barrier sits behind
+  // 16 queued MFMAs.
+  issue(0);
+  issue(1);
+  issue(2);
+  issue(3);
+  __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt(24): loads of step 0 have landed
+  __syncthreads();
+  u32x4 a0[4], b0[4], a1[4], b1[4];
+  read_frags(0, 0, a0, b0);
+  for (int64_t kt = 0; kt < nkt; ++kt) {
+    read_frags(kt, 1, a1, b1);
+    mma(a0, b0);
+    __builtin_amdgcn_s_waitcnt(0x4070);  // vmcnt(16), lgkmcnt(0)
+    __syncthreads();
+    issue(kt + 4);
+    read_frags(kt + 1, 0, a0, b0);
+    mma(a1, b1);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0), lgkmcnt(0): drain the look-ahead
+
+  // H[i][j] += alpha * acc for i >= j; MFMA row m <-> channel i0 + 32(4wm+f) + m,
+  // MFMA column n <-> channel j0 + 32(4wn+g) + n: 32 lanes write 128 contiguous bytes.
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int64_t j = j0 + 32 * (4 * wn + g) + lo;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = 8 * (r >> 2) + 4 * hi + (r & 3);
+        const int64_t i = i0 + 32 * (4 * wm + f) + m;
+        if (i < a.b && j <= i) {
+          float* ptr = a.H + i * a.b + j;
+          *ptr += a.alpha * acc[f][g][r];
+        }
+      }
+    }
+}
+
 thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc,
                               thanos_dtype xdt, int64_t n_tok, int64_t ldx, float alpha) {
   if (n_tok == 0) return THANOS_OK;
@@ -223,10 +388,11 @@ thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc
   a.nt = (int)ceil_div(b, kSyTile);
   a.ntiles = a.nt * (a.nt + 1) / 2;
   const bool vec = (reinterpret_cast<uintptr_t>(Xc) % 16 == 0) && (ldx % 8 == 0) && (b % 8 == 0);
-  const size_t smem = 2 * kSyOct * 512 * sizeof(u32x4);  // 128 KB
+  const size_t smem = vec ? (size_t)kDmaStages * kDmaStageBytes            // 136 KB
+                          : 2 * kSyOct * 512 * sizeof(u32x4);              // 128 KB
   void (*kern)(SyrkArgs);
-  if (xdt == THANOS_BF16) kern = vec ? k_syrk16<true, true> : k_syrk16<true, false>;
-  else kern = vec ? k_syrk16<false, true> : k_syrk16<false, false>;
+  if (xdt == THANOS_BF16) kern = vec ? k_syrk16_dma<true> : k_syrk16<true, false>;
+  else kern = vec ? k_syrk16_dma<false> : k_syrk16<false, false>;
   THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
   hipLaunchKernelGGL(kern, dim3((unsigned)a.ntiles), dim3(256), smem, s, a);
