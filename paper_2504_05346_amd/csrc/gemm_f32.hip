@@ -28,19 +28,27 @@ __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs g) {
   gemm_tile<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, 0, g.K, g.vec_a, g.vec_b);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  // Per 32x32 MFMA tile: 16 loads, then 16 stores.  A load placed right behind a store to the
+  // same array would have to wait for it, which serialises 64 memory round trips per thread.
 #pragma unroll
   for (int f = 0; f < 2; ++f)
 #pragma unroll
     for (int gg = 0; gg < 2; ++gg) {
       const int col = acc_col(wn, gg, lane);
+      float old[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = acc_row(wm, f, r, lane);
-        if (row < m_ext && col < n_ext) {
-          float* p = g.C + (int64_t)(m0 + row) * g.ldc + (n0 + col);
-          const float v = g.alpha * acc.v[f][gg][r];
-          *p = (g.beta == 0.f) ? v : g.beta * (*p) + v;
-        }
+        old[r] = (g.beta != 0.f && row < m_ext && col < n_ext)
+                     ? g.C[(int64_t)(m0 + row) * g.ldc + (n0 + col)]
+                     : 0.f;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = acc_row(wm, f, r, lane);
+        if (row < m_ext && col < n_ext)
+          g.C[(int64_t)(m0 + row) * g.ldc + (n0 + col)] =
+              g.beta * old[r] + g.alpha * acc.v[f][gg][r];
       }
     }
 }

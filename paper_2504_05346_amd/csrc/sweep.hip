@@ -318,7 +318,7 @@ struct SolveSmem {
 };
 
 template <int CPL, int RPL, int SEL, int WPB>
-__global__ __launch_bounds__(64 * WPB) void k_solve(SolveArgs a) {
+__global__ __launch_bounds__(64 * WPB, (RPL == 1 ? 2 : 1)) void k_solve(SolveArgs a) {
   constexpr int SMAX = 64 * RPL;
   __shared__ SolveSmem<CPL, RPL> smem[WPB];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -557,20 +557,30 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a) {
   gemm_tile<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.bw, a.vec_a, a.vec_b);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
   const int64_t j2 = a.j1 + a.bw;
+  const bool in_block = n0 < j2;  // only tiles that overlap the block's own columns hold masks
+  // per 32x32 MFMA tile: 16 loads, then 16 stores (see k_gemm_f32)
 #pragma unroll
   for (int f = 0; f < 2; ++f)
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int col = acc_col(wn, g, lane);
       const int64_t cg = n0 + col;
+      float old[16];
+      bool mk[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = acc_row(wm, f, r, lane);
+        const bool ok = row < m_ext && col < n_ext;
+        const int64_t idx = (m0 + row) * a.b + cg;
+        old[r] = ok ? a.W[idx] : 0.f;
+        mk[r] = (ok && in_block && cg < j2) ? (a.mask[idx] != 0) : false;
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = acc_row(wm, f, r, lane);
         if (row < m_ext && col < n_ext) {
           const int64_t idx = (m0 + row) * a.b + cg;
-          float w = a.W[idx] - acc.v[f][g][r];
-          if (cg < j2 && a.mask[idx]) w = 0.f;
-          a.W[idx] = w;
+          a.W[idx] = mk[r] ? 0.f : old[r] - acc.v[f][g][r];
         }
       }
     }

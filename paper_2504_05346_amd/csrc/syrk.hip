@@ -250,12 +250,18 @@ __device__ __forceinline__ void dma_row(const u32x4& rsrc, uint32_t lds_addr, ui
       : "memory");
 }
 
-template <bool BF16>
-__global__ __launch_bounds__(256) void k_syrk16_dma(SyrkArgs a) {
+// NW = 8 wavefronts (two per SIMD): wavefront tile 128 x 64, so that one wavefront of a SIMD
+// can fetch operands / wait at the barrier while the other one feeds the matrix core.
+// NW = 4: wavefront tile 128 x 128 (fewer LDS reads per MFMA, nothing to overlap with).
+template <bool BF16, int NW>
+__global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
+  constexpr int WN = NW / 2;          // wavefronts along the column panel
+  constexpr int GN = 8 / WN;          // 32-wide MFMA tiles per wavefront along columns
+  constexpr int RPW = kDmaKT / NW;    // token rows each wavefront loads per k-step
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int lo = lane & 31, hi = lane >> 5;
 
   const int nwg = a.ntiles;
@@ -275,21 +281,21 @@ __global__ __launch_bounds__(256) void k_syrk16_dma(SyrkArgs a) {
   const int s16 = lane & 15, g16 = (lane & 31) >> 4;
   const int lane_off = (8 * hi + (s16 >> 2)) * kDmaRow + (16 * g16 + 4 * (s16 & 3)) * 2;
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][GN];
 #pragma unroll
   for (int f = 0; f < 4; ++f)
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
+    for (int g = 0; g < GN; ++g)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[f][g][r] = 0.f;
 
   const int64_t nkt = (a.n_tok + kDmaKT - 1) / kDmaKT;
 
-  // Issue the 8 row loads of this wavefront for k-step kt (rows 8*wave .. 8*wave+7 of the
-  // step).  Steps past the end get an empty descriptor: every lane is out of range, nothing is
-  // read and zeros are written, so the wait counts below stay uniform.
+  // Issue the row loads of this wavefront for k-step kt.  Steps past the end get an empty
+  // descriptor: every lane is out of range, nothing is read and zeros are written, so the wait
+  // counts below stay uniform.
   auto issue = [&](int64_t kt) {
-    const int64_t t0 = kt * kDmaKT + 8 * wave;
+    const int64_t t0 = kt * kDmaKT + RPW * wave;
     int64_t rem_bytes = ((a.n_tok - t0 - 1) * a.ldx + a.b) * 2;
     const uint16_t* base = a.X + t0 * a.ldx;
     if (t0 >= a.n_tok) {
@@ -304,25 +310,25 @@ __global__ __launch_bounds__(256) void k_syrk16_dma(SyrkArgs a) {
     rs.z = __builtin_amdgcn_readfirstlane(nrec);
     rs.w = 0x00020000u;
     const uint32_t dst = lds_base + (uint32_t)((int)(kt % kDmaStages) * kDmaStageBytes +
-                                               (8 * wave) * kDmaRow);
+                                               (RPW * wave) * kDmaRow);
     const uint32_t row_bytes = __builtin_amdgcn_readfirstlane((uint32_t)(a.ldx * 2));
 #pragma unroll
-    for (int r = 0; r < 8; ++r)
+    for (int r = 0; r < RPW; ++r)
       dma_row(rs, __builtin_amdgcn_readfirstlane(dst + r * kDmaRow), voff, r * row_bytes);
   };
-  auto read_frags = [&](int64_t kt, int ks, u32x4 (&af)[4], u32x4 (&bf)[4]) {
+  auto read_frags = [&](int64_t kt, int ks, u32x4 (&af)[4], u32x4 (&bf)[GN]) {
     const char* st = lds + (int)(kt % kDmaStages) * kDmaStageBytes + lane_off + ks * 16 * kDmaRow;
 #pragma unroll
     for (int f = 0; f < 4; ++f) af[f] = frag_read_tr(st, (32 * (4 * wm + f)) * 2);
 #pragma unroll
-    for (int g = 0; g < 4; ++g) bf[g] = frag_read_tr(st, 512 + (32 * (4 * wn + g)) * 2);
+    for (int g = 0; g < GN; ++g) bf[g] = frag_read_tr(st, 512 + (32 * (GN * wn + g)) * 2);
   };
-  auto mma = [&](const u32x4 (&af)[4], const u32x4 (&bf)[4]) {
+  auto mma = [&](const u32x4 (&af)[4], const u32x4 (&bf)[GN]) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int f = 0; f < 4; ++f)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) acc[f][g] = mfma16<BF16>(af[f], bf[g], acc[f][g]);
+      for (int g = 0; g < GN; ++g) acc[f][g] = mfma16<BF16>(af[f], bf[g], acc[f][g]);
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -331,19 +337,21 @@ __global__ __launch_bounds__(256) void k_syrk16_dma(SyrkArgs a) {
   //   done | barrier | issue loads of kt+4 into the stage of kt | read slice 0 of kt+1 |
   //   MFMA slice 1 of kt.
   // Every MFMA group has its operands fetched one group earlier, and the barrier sits behind
-  // 16 queued MFMAs.
+  // a group of queued MFMAs.  vmcnt(n): at most n of this wavefront's loads still pending.
+  constexpr int kWaitPrologue = (RPW * 3 & 15) | ((RPW * 3 >> 4) << 14) | 0x0F70;  // 3 steps pending
+  constexpr int kWaitLoop = (RPW * 2 & 15) | ((RPW * 2 >> 4) << 14) | 0x0070;      // 2 steps, lgkm 0
   issue(0);
   issue(1);
   issue(2);
   issue(3);
-  __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt(24): loads of step 0 have landed
+  __builtin_amdgcn_s_waitcnt(kWaitPrologue);
   __syncthreads();
-  u32x4 a0[4], b0[4], a1[4], b1[4];
+  u32x4 a0[4], b0[GN], a1[4], b1[GN];
   read_frags(0, 0, a0, b0);
   for (int64_t kt = 0; kt < nkt; ++kt) {
     read_frags(kt, 1, a1, b1);
     mma(a0, b0);
-    __builtin_amdgcn_s_waitcnt(0x4070);  // vmcnt(16), lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(kWaitLoop);
     __syncthreads();
     issue(kt + 4);
     read_frags(kt + 1, 0, a0, b0);
@@ -352,20 +360,25 @@ __global__ __launch_bounds__(256) void k_syrk16_dma(SyrkArgs a) {
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0), lgkmcnt(0): drain the look-ahead
 
   // H[i][j] += alpha * acc for i >= j; MFMA row m <-> channel i0 + 32(4wm+f) + m,
-  // MFMA column n <-> channel j0 + 32(4wn+g) + n: 32 lanes write 128 contiguous bytes.
+  // MFMA column n <-> channel j0 + 32(GN wn+g) + n: 32 lanes write 128 contiguous bytes.
+  // per 32x32 MFMA tile: 16 loads, then 16 stores (a load behind a store would wait for it)
 #pragma unroll
   for (int f = 0; f < 4; ++f)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int64_t j = j0 + 32 * (4 * wn + g) + lo;
+    for (int g = 0; g < GN; ++g) {
+      const int64_t j = j0 + 32 * (GN * wn + g) + lo;
+      float old[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = 8 * (r >> 2) + 4 * hi + (r & 3);
         const int64_t i = i0 + 32 * (4 * wm + f) + m;
-        if (i < a.b && j <= i) {
-          float* ptr = a.H + i * a.b + j;
-          *ptr += a.alpha * acc[f][g][r];
-        }
+        old[r] = (i < a.b && j <= i) ? a.H[i * a.b + j] : 0.f;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = 8 * (r >> 2) + 4 * hi + (r & 3);
+        const int64_t i = i0 + 32 * (4 * wm + f) + m;
+        if (i < a.b && j <= i) a.H[i * a.b + j] = old[r] + a.alpha * acc[f][g][r];
       }
     }
 }
@@ -391,11 +404,12 @@ thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc
   const size_t smem = vec ? (size_t)kDmaStages * kDmaStageBytes            // 136 KB
                           : 2 * kSyOct * 512 * sizeof(u32x4);              // 128 KB
   void (*kern)(SyrkArgs);
-  if (xdt == THANOS_BF16) kern = vec ? k_syrk16_dma<true> : k_syrk16<true, false>;
-  else kern = vec ? k_syrk16_dma<false> : k_syrk16<false, false>;
+  constexpr int kNW = 8;
+  if (xdt == THANOS_BF16) kern = vec ? k_syrk16_dma<true, kNW> : k_syrk16<true, false>;
+  else kern = vec ? k_syrk16_dma<false, kNW> : k_syrk16<false, false>;
   THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-  hipLaunchKernelGGL(kern, dim3((unsigned)a.ntiles), dim3(256), smem, s, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)a.ntiles), dim3(vec ? 64 * kNW : 256), smem, s, a);
   THANOS_LAUNCH_CHECK();
   return THANOS_OK;
 }
