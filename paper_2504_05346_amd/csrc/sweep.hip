@@ -480,30 +480,44 @@ __global__ __launch_bounds__(64 * WPB, (RPL == 1 ? 2 : 1)) void k_solve(SolveArg
         u[r] = fmaf(-l[r], yk, u[r]);
       }
       WAVE_SYNC();
-      // pivot column broadcast: register j <-> column k0 + j
+      // pivot column broadcast: register j <-> column k0 + j.  Only registers that still hold
+      // live columns (j < s - k0) are touched, in chunks of 16.
       const f32x4* cb = reinterpret_cast<const f32x4*>(&sm.col[t][k0]);
+      const int wact = s - k0;
       if (t < 3) {
 #pragma unroll
-        for (int j4 = 0; j4 < SMAX / 4; ++j4) {
-          const f32x4 lb = cb[j4];
+        for (int c16 = 0; c16 < SMAX / 16; ++c16) {
+          if (16 * c16 < wact) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int j = 4 * j4 + e;
-            if (j > t) {
+            for (int j4 = 4 * c16; j4 < 4 * c16 + 4; ++j4) {
+              const f32x4 lb = cb[j4];
 #pragma unroll
-              for (int r = 0; r < RPL; ++r) A[r][j] = fmaf(-l[r], lb[e], A[r][j]);
+              for (int e = 0; e < 4; ++e) {
+                const int j = 4 * j4 + e;
+                if (j > t) {
+#pragma unroll
+                  for (int r = 0; r < RPL; ++r) A[r][j] = fmaf(-l[r], lb[e], A[r][j]);
+                }
+              }
             }
           }
         }
       } else {
 #pragma unroll
-        for (int j4 = 1; j4 < SMAX / 4; ++j4) {
-          const f32x4 lb = cb[j4];
+        for (int c16 = 0; c16 < SMAX / 16; ++c16) {
+          if (16 * c16 < wact + 4) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int j = 4 * j4 + e;
+            for (int j4 = 4 * c16; j4 < 4 * c16 + 4; ++j4) {
+              if (j4 >= 1) {
+                const f32x4 lb = cb[j4];
 #pragma unroll
-            for (int r = 0; r < RPL; ++r) A[r][j - 4] = fmaf(-l[r], lb[e], A[r][j]);
+                for (int e = 0; e < 4; ++e) {
+                  const int j = 4 * j4 + e;
+#pragma unroll
+                  for (int r = 0; r < RPL; ++r) A[r][j - 4] = fmaf(-l[r], lb[e], A[r][j]);
+                }
+              }
+            }
           }
         }
 #pragma unroll
@@ -531,6 +545,171 @@ __global__ __launch_bounds__(64 * WPB, (RPL == 1 ? 2 : 1)) void k_solve(SolveArg
     const int col = lane + 64 * r;
     if (col < a.bw) lam_g[col] = sm.wrow[col];
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Mask + per-row solve for systems of up to 128 unknowns: one workgroup of 128 threads (two
+// wavefronts) per row of W, thread t <-> block column t <-> row t of R_hat (128 registers).
+// Same symmetric Gauss-Jordan elimination and register renaming by panels of 4 as k_solve, in
+// its square-root-free form  A[rho][j] -= (A[rho][k] / d) * A[j][k],  so that the broadcast
+// column needs no scaling.  The pivot column travels through LDS (one barrier per pivot).
+// Only the registers that still hold live columns (j < s - 4*panel) are touched, in chunks of
+// 16, so a system of s unknowns costs ~s^2/2 fused multiply-adds per thread, not s*128.
+template <int SEL>
+__global__ __launch_bounds__(128, 3) void k_solve_wide(SolveArgs a) {
+  constexpr int SMAX = 128;
+  __shared__ __attribute__((aligned(16))) float col[2][4][SMAX + 32];  // tail stays zero
+  __shared__ float ukb[2][4];
+  __shared__ float wrow[SMAX];
+  __shared__ float key[SMAX];
+  __shared__ int q[SMAX];
+  __shared__ int cnt[2];
+  __shared__ int eqc[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t i = blockIdx.x;
+  const float* wrow_g = a.W + i * a.b + a.j1;
+
+  const float w = (tid < a.bw) ? wrow_g[tid] : 0.f;
+  wrow[tid] = w;
+  for (int e = tid; e < 2 * 4 * (SMAX + 32); e += 128) (&col[0][0][0])[e] = 0.f;
+  bool sel = false;
+  if (SEL == SEL_GIVEN) {
+    sel = (tid < a.bw) && a.mask_in[i * a.b + a.j1 + tid] != 0;
+  } else if (SEL == SEL_NM) {
+    key[tid] = (tid < a.bw) ? fabsf(w) * a.sx[a.j1 + tid] : 0.f;
+    __syncthreads();
+    if (tid < a.bw) {
+      const int g0 = (tid / a.m) * a.m;
+      const float mine = key[tid];
+      int rank = 0;
+      for (int e = 0; e < a.m; ++e) {
+        const float o = key[g0 + e];
+        rank += (o < mine || (o == mine && g0 + e < tid)) ? 1 : 0;
+      }
+      sel = rank < a.n;
+    }
+  } else {  // SEL_THRESHOLD
+    const bool none = a.st->none != 0;
+    const unsigned int tau = a.st->tau;
+    const long long need_eq = a.st->need_eq;
+    const bool in = (tid < a.bw) && !none;
+    const unsigned int kk = in ? metric_key(w, a.sx[a.j1 + tid]) : 0xffffffffu;
+    const bool lt = in && kk < tau;
+    const bool eq = in && kk == tau;
+    const unsigned long long eqb = __ballot(eq);
+    if (lane == 0) eqc[wave] = __popcll(eqb);
+    __syncthreads();
+    const long long my = (long long)a.row_eq[i] + (wave ? eqc[0] : 0) +
+                         __popcll(eqb & ((1ull << lane) - 1ull));
+    sel = lt || (eq && my < need_eq);
+  }
+  const unsigned long long bal = __ballot(sel);
+  if (lane == 0) cnt[wave] = __popcll(bal);
+  __syncthreads();
+  const int s = cnt[0] + cnt[1];
+  const int myrank = (wave ? cnt[0] : 0) + __popcll(bal & ((1ull << lane) - 1ull));
+  if (sel) q[myrank] = tid;
+  if (tid < a.bw) a.mask_out[i * a.b + a.j1 + tid] = sel ? 1 : 0;
+  if (SEL == SEL_THRESHOLD) {
+    if (tid == 0 && s > 0) atomicAdd(&a.st_rw->blk_count, s);
+  }
+  float* lam_g = a.Lam + i * a.ldl;
+  if (s == 0) {
+    if (tid < a.bw) lam_g[tid] = 0.f;
+    return;
+  }
+  __syncthreads();
+
+  // ---- gather R_hat: A[j] = G[q_j][q_rho] (= G[q_rho][q_j]) ----
+  const float* G = a.P + a.j1 * a.b + a.j1;
+  const int rho = tid;
+  const int qr = (rho < s) ? q[rho] : 0;
+  float u = (rho < s) ? wrow[qr] : 0.f;
+  float dinv = 0.f;
+  float A[SMAX];
+#pragma unroll
+  for (int j = 0; j < SMAX; ++j) {
+    float v = 0.f;
+    if (j < s) {
+      const float* grow = G + (int64_t)q[j] * a.b;
+      if (rho < s) v = grow[qr];
+    }
+    A[j] = v;
+  }
+
+  // ---- elimination ----
+  bool bad = false;
+  const int npanel = (s + 3) >> 2;
+  for (int pnl = 0; pnl < npanel; ++pnl) {
+    const int k0 = 4 * pnl;
+    const int wact = s - k0;  // live registers: columns k0 .. s-1
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int k = k0 + t;
+      float* cb = col[pnl & 1][t];
+      cb[rho] = A[t];
+      if (rho == k) ukb[pnl & 1][t] = u;
+      __syncthreads();
+      const float d = cb[k];
+      const float uk = ukb[pnl & 1][t];
+      float rd = 0.f;
+      if (k < s) {
+        if (d > 0.f) rd = 1.f / d;
+        else bad = true;
+      }
+      float m = A[t] * rd;
+      if (rho == k) {
+        dinv = rd;
+        m = 0.f;  // the pivot row itself is not modified
+      }
+      u = fmaf(-m, uk, u);
+      const f32x4* cv = reinterpret_cast<const f32x4*>(&cb[k0]);  // register j <-> column k0 + j
+      if (t < 3) {
+#pragma unroll
+        for (int c16 = 0; c16 < SMAX / 16; ++c16) {
+          if (16 * c16 < wact) {
+#pragma unroll
+            for (int j4 = 4 * c16; j4 < 4 * c16 + 4; ++j4) {
+              const f32x4 lb = cv[j4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int j = 4 * j4 + e;
+                if (j > t) A[j] = fmaf(-m, lb[e], A[j]);
+              }
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int c16 = 0; c16 < SMAX / 16; ++c16) {
+          if (16 * c16 < wact + 4) {
+#pragma unroll
+            for (int j4 = 4 * c16; j4 < 4 * c16 + 4; ++j4) {
+              if (j4 >= 1) {
+                const f32x4 lb = cv[j4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int j = 4 * j4 + e;
+                  A[j - 4] = fmaf(-m, lb[e], A[j]);
+                }
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) A[SMAX - 4 + e] = 0.f;
+      }
+    }
+  }
+  if (bad && tid == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
+
+  // ---- lambda row: zeros except lambda_k = u_k / d_k at column q_k ----
+  __syncthreads();
+  wrow[tid] = 0.f;
+  __syncthreads();
+  if (rho < s) wrow[qr] = u * dinv;
+  __syncthreads();
+  if (tid < a.bw) lam_g[tid] = wrow[tid];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -645,7 +824,7 @@ static void launch_solve(hipStream_t s, const SolveArgs& a, int smax) {
   } else if (smax <= 64) {
     hipLaunchKernelGGL((k_solve<2, 1, SEL, 4>), dim3((unsigned)ceil_div(a.c, 4)), dim3(256), 0, s, a);
   } else {
-    hipLaunchKernelGGL((k_solve<2, 2, SEL, 2>), dim3((unsigned)ceil_div(a.c, 2)), dim3(128), 0, s, a);
+    hipLaunchKernelGGL((k_solve_wide<SEL>), dim3((unsigned)a.c), dim3(128), 0, s, a);
   }
 }
 
