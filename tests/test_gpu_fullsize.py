@@ -1,0 +1,147 @@
+"""GPU parity at the benchmark's full size (4096 x 11008, 262144 tokens), in the launch
+configuration bench.py times.  The oracle cannot redo the whole layer in seconds, so outputs
+are checked on samples it can compute one by one, and through properties that hold at any size:
+  * Hessian: sampled entries against float64 dot products of the same fp16 columns;
+  * factor: U upper triangular, U^T (U (H_d e_j)) = e_j on sampled columns, and U against the
+    oracle's own factor of the same matrix;
+  * 2:4 sweep: exact pattern and zeros on the whole layer, sampled rows against the oracle;
+  * unstructured sweep: exact count, the first block's mask against a float32 partition of the
+    full metric (ties included), sampled rows against the oracle under the GPU's own mask.
+"""
+import types
+
+import numpy as np
+import pytest
+
+from oracle import thanos_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+C, B_IN, T = 4096, 11008, 262144
+BLOCK, DAMP = 128, 0.01
+
+
+@pytest.fixture(scope="module")
+def layer():
+    import torch
+    import bench
+    import paper_2504_05346_amd as th
+    args = types.SimpleNamespace(c=C, b=B_IN, tokens=T)
+    print("generating the full-size layer on the device", flush=True)
+    W, X = bench.make_inputs(args, torch)
+    H = torch.zeros((B_IN, B_IN), dtype=torch.float32, device="cuda")
+    th.thanos_hessian_accumulate(H, X)           # one call, as bench.py does
+    torch.cuda.synchronize()
+    return types.SimpleNamespace(W=W, X=X, H=H)
+
+
+def _prune(layer, mode, **kw):
+    import torch
+    import paper_2504_05346_amd as th
+    o = th.PruneOpts(mode=th.THANOS_NM if mode == "nm" else th.THANOS_UNSTRUCTURED,
+                     sparsity=0.5, n=2, m=4, block_size=BLOCK, damping=DAMP)
+    ws = torch.empty((th.thanos_prune_workspace_bytes(C, B_IN, o),), dtype=torch.uint8,
+                     device="cuda")
+    Wo = torch.empty((C, B_IN), dtype=torch.float32, device="cuda")
+    M = torch.empty((C, B_IN), dtype=torch.uint8, device="cuda")
+    info = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    th.thanos_prune_layer(layer.W, layer.H, o, Wo, None, M, ws, info)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    return Wo, M
+
+
+@pytest.fixture(scope="module")
+def host(layer):
+    """Host copies and the oracle's own factor of the GPU Hessian (float64)."""
+    print("oracle factor of the 11008 x 11008 Hessian", flush=True)
+    Hl = layer.H.cpu().numpy().astype(np.float64)
+    H = np.tril(Hl) + np.tril(Hl, -1).T
+    U = orc.inverse_factor(orc.damped(H, DAMP))
+    return types.SimpleNamespace(H=H, U=U)
+
+
+def test_hessian_sampled_entries(layer):
+    g = np.random.default_rng(0)
+    idx = g.integers(0, B_IN, size=(48, 2))
+    idx = np.vstack([idx, np.stack([np.arange(0, B_IN, 997)] * 2, axis=1),
+                     [[B_IN - 1, 0], [B_IN - 1, B_IN - 1], [255, 256], [256, 255]]])
+    cols = np.unique(idx)
+    Xc = layer.X[:, cols.tolist()].cpu().numpy().astype(np.float64)       # T x ncols
+    pos = {c: k for k, c in enumerate(cols)}
+    Hs = layer.H.cpu().numpy()
+    for i, j in idx:
+        i, j = max(i, j), min(i, j)                                        # lower triangle
+        ref = float(Xc[:, pos[i]] @ Xc[:, pos[j]])
+        scale = np.sqrt(float(Xc[:, pos[i]] @ Xc[:, pos[i]]) * float(Xc[:, pos[j]] @ Xc[:, pos[j]]))
+        assert abs(float(Hs[i, j]) - ref) <= 1e-5 * scale, (i, j, Hs[i, j], ref)
+
+
+def test_factor_properties_and_oracle(layer, host):
+    import torch
+    import paper_2504_05346_amd as th
+    b = B_IN
+    U = torch.empty((b, b), dtype=torch.float32, device="cuda")
+    xn2 = torch.empty((b,), dtype=torch.float32, device="cuda")
+    ws = torch.empty((th.thanos_factor_workspace_bytes(b),), dtype=torch.uint8, device="cuda")
+    info = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    th.thanos_factor(layer.H, DAMP, U, xn2, ws, info)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    Ug = U.cpu().numpy().astype(np.float64)
+    assert np.all(np.tril(Ug, -1) == 0.0)
+    np.testing.assert_array_equal(xn2.cpu().numpy(), np.diag(host.H).astype(np.float32))
+    Hd = orc.damped(host.H, DAMP)
+    for j in (0, 1, 127, 128, 5000, 11007):
+        e = Ug.T @ (Ug @ Hd[:, j])
+        e[j] -= 1.0
+        assert np.max(np.abs(e)) < 5e-3, j
+    assert np.linalg.norm(Ug - host.U) <= 5e-4 * np.linalg.norm(host.U)
+
+
+def test_nm_sweep_full_layer(layer, host):
+    Wo, M = _prune(layer, "nm")
+    import torch
+    grp = M.view(C, B_IN // 4, 4).sum(dim=2)
+    assert bool((grp == 2).all())
+    assert float(Wo[M == 1].abs().max()) == 0.0
+    rows = [0, 1, 777, 2048, 4095]
+    W = layer.W[rows].cpu().numpy()
+    Wg = Wo[rows].cpu().numpy().astype(np.float64)
+    Mg = M[rows].cpu().numpy()
+    Wref, Mref, mg = None, None, None
+    Wref, Mref = orc.prune_fast(W, host.H, mode="nm", n=2, m=4, B=BLOCK, damp=DAMP, U=host.U)
+    same = np.all(Mg == Mref, axis=1)
+    assert (Mg != Mref).mean() < 1e-4
+    assert same.sum() >= len(rows) - 2
+    for k in np.flatnonzero(same):
+        assert np.linalg.norm(Wg[k] - Wref[k]) <= 1e-3 * np.linalg.norm(Wref[k])
+    # rows whose mask differs somewhere: compare under the GPU's own mask
+    Wt, _ = orc.prune_fast(W, host.H, mode="nm", n=2, m=4, B=BLOCK, damp=DAMP, U=host.U, mask_in=Mg)
+    assert np.linalg.norm(Wg - Wt) <= 1e-3 * np.linalg.norm(Wt)
+
+
+def test_unstructured_sweep_full_layer(layer, host):
+    Wo, M = _prune(layer, "unstructured")
+    assert int(M.sum().item()) == C * B_IN // 2
+    assert float(Wo[M == 1].abs().max()) == 0.0
+    # first block: the global residual mask is the r smallest of the fp32 metric of the input
+    W32 = layer.W.float().cpu().numpy()
+    sx = np.sqrt(np.diag(host.H).astype(np.float32))
+    mu = (np.abs(W32) * sx[None, :]).astype(np.float32)
+    r = C * B_IN // 2
+    tau = np.partition(mu.ravel(), r - 1)[r - 1]
+    less = mu < tau
+    need = r - int(less.sum())
+    ties = np.flatnonzero((mu == tau).ravel())[:need]                    # row-major order
+    Mref = less.copy().ravel()
+    Mref[ties] = True
+    Mref = Mref.reshape(C, B_IN)[:, :BLOCK]
+    np.testing.assert_array_equal(M[:, :BLOCK].cpu().numpy().astype(bool), Mref)
+    rows = [0, 1234, 4095]
+    W = layer.W[rows].cpu().numpy()
+    Mg = M[rows].cpu().numpy()
+    Wt, _ = orc.prune_fast(W, host.H, mode="unstructured", p=0.5, B=BLOCK, damp=DAMP, U=host.U,
+                           mask_in=Mg)
+    Wg = Wo[rows].cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(Wg - Wt) <= 1e-3 * np.linalg.norm(Wt)
