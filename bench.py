@@ -47,6 +47,9 @@ def parse_args():
                     help="number of thanos_hessian_accumulate calls the tokens are split into")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--phases-only", action="store_true", help="skip the oracle, print phases")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run one plain 1 GiB device copy first (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -115,6 +118,13 @@ def main():
     th.lib()
 
     W, X = make_inputs(args, torch)
+    if args.copy_probe:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     c, b, T = args.c, args.b, args.tokens
     o = th.PruneOpts(mode=th.THANOS_NM if args.mode == "nm" else th.THANOS_UNSTRUCTURED,
                      sparsity=args.sparsity, n=args.n, m=args.m, block_size=args.block,

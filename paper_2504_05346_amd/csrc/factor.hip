@@ -11,9 +11,12 @@
 // U = J L^{-1} J.  So: (1) reversed, zero/identity-padded copy A' (ld = bp, a multiple of the
 // factor block NB = 128); (2) right-looking blocked Cholesky: diagonal block in one workgroup
 // (which also produces the inverse of the diagonal block), panel = product with that inverse,
-// trailing update = rank-NB product on the matrix cores; (3) L^{-1} by recursive doubling over
+// trailing update on the matrix cores, two-level (rank NB inside an outer block of 4 factor
+// blocks, rank 4 NB for everything right of it); (3) L^{-1} by recursive doubling over
 // block pairs, X21 = -Linv22 * (L21 * Linv11), two products per level; (4) U = J L^{-1} J.
 // Everything is fp32.
+#include <algorithm>
+
 #include "gemm_tile.h"
 
 namespace thanos {
@@ -305,6 +308,11 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
                      s, H, b, lam, Ap, bp);
   THANOS_LAUNCH_CHECK();
 
+  // Two-level blocking: inside an outer block of kOuter factor blocks the trailing update of a
+  // step only reaches the columns of that outer block (narrow, K = NB); everything to the right
+  // gets one update per outer block with K = kOuter*NB, which reads and writes the trailing
+  // matrix kOuter times less often and runs the matrix cores on long reductions.
+  constexpr int kOuter = 4;
   for (int k = 0; k < nb; ++k) {
     hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, s, Ap, Linv, bp, k, b, info);
     THANOS_LAUNCH_CHECK();
@@ -312,14 +320,29 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
     if (rem <= 0) break;
     float* panel = Ap + ((int64_t)(k + 1) * NB) * bp + (int64_t)k * NB;
     const float* dinv = Linv + ((int64_t)k * NB) * bp + (int64_t)k * NB;
-    // L_ik = A_ik * Linv_kk^T  (in place)
+    // L_ik = A_ik * Linv_kk^T  (in place, all rows below the diagonal block)
     thanos_status st = gemm_f32(s, false, false, rem, NB, NB, 1.f, panel, bp, dinv, bp, 0.f,
                                 panel, bp, false);
     if (st != THANOS_OK) return st;
-    // A_ij -= L_ik L_jk^T on the lower tiles of the trailing matrix
-    float* trail = Ap + ((int64_t)(k + 1) * NB) * bp + (int64_t)(k + 1) * NB;
-    st = gemm_f32(s, false, false, rem, rem, NB, -1.f, panel, bp, panel, bp, 1.f, trail, bp, true);
-    if (st != THANOS_OK) return st;
+    const int ob_begin = (k / kOuter) * kOuter;
+    const int ob_end = std::min(nb, ob_begin + kOuter);
+    // narrow: A_ij -= L_ik L_jk^T for block columns k < j < ob_end, lower tiles
+    const int64_t ncols = (int64_t)(ob_end - (k + 1)) * NB;
+    if (ncols > 0) {
+      float* trail = Ap + ((int64_t)(k + 1) * NB) * bp + (int64_t)(k + 1) * NB;
+      st = gemm_f32(s, false, false, rem, ncols, NB, -1.f, panel, bp, panel, bp, 1.f, trail, bp,
+                    true);
+      if (st != THANOS_OK) return st;
+    }
+    // wide: after the last step of an outer block, everything right of it in one product
+    if (k + 1 == ob_end && ob_end < nb) {
+      const int64_t rest = bp - (int64_t)ob_end * NB;
+      const int64_t kk = (int64_t)(ob_end - ob_begin) * NB;
+      const float* lp = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_begin * NB;
+      float* trail = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_end * NB;
+      st = gemm_f32(s, false, false, rest, rest, kk, -1.f, lp, bp, lp, bp, 1.f, trail, bp, true);
+      if (st != THANOS_OK) return st;
+    }
   }
 
   for (int S = 1; S < nb; S *= 2) {

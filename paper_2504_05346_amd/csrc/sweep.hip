@@ -714,29 +714,34 @@ __global__ __launch_bounds__(128, 3) void k_solve_wide(SolveArgs a) {
 
 // ------------------------------------------------------------------------------------------
 // W[:, j1:b] -= Lam * P[j1:j2, j1:b]; removed weights of the block become exact zeros.
+// W[:, col0:col_end] -= Lam[:, 0:K] * P[prow0:prow0+K, col0:col_end]; entries of the column
+// range [zj1, zj2) whose mask byte is set are written as exact zeros.
 struct UpdateArgs {
   float* W;
-  const float* Lam;
+  const float* Lam;     // c x K multipliers, row stride ldl
   const float* P;
   const uint8_t* mask;
-  int64_t c, b, j1;
-  int bw, ldl, vec_a, vec_b;
+  int64_t c, b;
+  int64_t prow0;        // first row of P (= first reduction index)
+  int64_t col0, col_end;
+  int64_t zj1, zj2;
+  int K, ldl, vec_a, vec_b;
 };
 
 __global__ __launch_bounds__(256) void k_update(UpdateArgs a) {
   __shared__ GemmSmem sm;
   const int64_t m0 = (int64_t)blockIdx.y * kTM;
-  const int64_t n0 = a.j1 + (int64_t)blockIdx.x * kTN;
+  const int64_t n0 = a.col0 + (int64_t)blockIdx.x * kTN;
   const int m_ext = (int)min((int64_t)kTM, a.c - m0);
-  const int n_ext = (int)min((int64_t)kTN, a.b - n0);
-  const float* A = a.Lam + m0 * a.ldl;        // (m,k) at A[m*ldl + k]
-  const float* Bm = a.P + a.j1 * a.b + n0;    // (k,n) at B[k*b + n]
+  const int n_ext = (int)min((int64_t)kTN, a.col_end - n0);
+  const float* A = a.Lam + m0 * a.ldl;          // (m,k) at A[m*ldl + k]
+  const float* Bm = a.P + a.prow0 * a.b + n0;   // (k,n) at B[k*b + n]
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.bw, a.vec_a, a.vec_b);
+  gemm_tile<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
-  const int64_t j2 = a.j1 + a.bw;
-  const bool in_block = n0 < j2;  // only tiles that overlap the block's own columns hold masks
+  const int64_t j2 = a.zj2;
+  const bool in_block = n0 < j2 && n0 + kTN > a.zj1;  // tile overlaps the columns holding masks
   // per 32x32 MFMA tile: 16 loads, then 16 stores (see k_gemm_f32)
 #pragma unroll
   for (int f = 0; f < 2; ++f)
@@ -752,7 +757,7 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a) {
         const bool ok = row < m_ext && col < n_ext;
         const int64_t idx = (m0 + row) * a.b + cg;
         old[r] = ok ? a.W[idx] : 0.f;
-        mk[r] = (ok && in_block && cg < j2) ? (a.mask[idx] != 0) : false;
+        mk[r] = (ok && in_block && cg >= a.zj1 && cg < j2) ? (a.mask[idx] != 0) : false;
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -782,10 +787,16 @@ static char* carve(char*& p, size_t bytes) {
   return q;
 }
 
+// Blocks whose selection only looks at their own columns (n:m, forced masks) are swept in
+// super-blocks of kSuper blocks: inside a super-block the update of a block only reaches the
+// end of the super-block, and everything right of it gets one update per super-block with a
+// kSuper times longer reduction (the multipliers of all its blocks are kept, c x kSuper*B).
+constexpr int kSuper = 8;
+
 size_t sweep_workspace_bytes(int64_t c, int64_t b, int B) {
   size_t n = 0;
   n += align_up((size_t)b * 4, 256);            // sx
-  n += align_up((size_t)c * B * 4, 256);        // Lam
+  n += align_up((size_t)c * B * kSuper * 4, 256);  // Lam
   n += align_up((size_t)b * b * 4, 256);        // P
   n += align_up(2048 * 4, 256);                 // hist
   n += align_up(sizeof(SelState), 256);         // state
@@ -797,7 +808,7 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B) {
   char* p = reinterpret_cast<char*>(ws);
   SweepWs w;
   w.sx = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
-  w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * 4));
+  w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * kSuper * 4));
   w.P = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
   w.hist = reinterpret_cast<unsigned int*>(carve(p, 2048 * 4));
   w.st = reinterpret_cast<SelState*>(carve(p, sizeof(SelState)));
@@ -865,8 +876,14 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   }
 
   const unsigned rows4 = (unsigned)ceil_div(c, 4);
+  const int super = unstructured ? 1 : kSuper;   // the global residual mask needs current weights
+  const int ldl = B * super;
   for (int64_t j1 = 0; j1 < b; j1 += B) {
     const int bw = (int)std::min<int64_t>(B, b - j1);
+    const int64_t blk = j1 / B;
+    const int64_t sb_start = (blk / super) * super * (int64_t)B;
+    const int64_t sb_end = std::min<int64_t>(b, sb_start + (int64_t)super * B);
+    const int64_t loff = j1 - sb_start;  // column of this block inside the multiplier buffer
     if (unstructured) {
       hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(1), 0, s, w.st);
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
@@ -889,7 +906,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.sx = w.sx;
     sa.mask_in = o->mask_in;
     sa.mask_out = mask;
-    sa.Lam = w.Lam;
+    sa.Lam = w.Lam + loff;
     sa.st = w.st;
     sa.st_rw = w.st;
     sa.row_eq = w.row_eq;
@@ -898,7 +915,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.b = b;
     sa.j1 = j1;
     sa.bw = bw;
-    sa.ldl = B;
+    sa.ldl = ldl;
     sa.n = o->n;
     sa.m = o->m;
     if (o->mask_in) {
@@ -910,12 +927,20 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     }
     THANOS_LAUNCH_CHECK();
 
-    UpdateArgs ua{W, w.Lam, w.P, mask, c, b, j1, bw, B,
-                  (B % 4 == 0) ? 1 : 0,
-                  aligned_b ? 1 : 0};
-    dim3 grid((unsigned)ceil_div(b - j1, kTN), (unsigned)ceil_div(c, kTM));
-    hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
-    THANOS_LAUNCH_CHECK();
+    {  // this block's update, up to the end of its super-block
+      UpdateArgs ua{W, w.Lam + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
+                    (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+      dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
+      hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
+      THANOS_LAUNCH_CHECK();
+    }
+    if (j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block, right of it
+      UpdateArgs ua{W, w.Lam, w.P, mask, c, b, sb_start, sb_end, b, 0, 0,
+                    (int)(sb_end - sb_start), ldl, (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+      dim3 grid((unsigned)ceil_div(b - sb_end, kTN), (unsigned)ceil_div(c, kTM));
+      hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
+      THANOS_LAUNCH_CHECK();
+    }
   }
 
   if (W_cast) {
