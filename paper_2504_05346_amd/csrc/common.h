@@ -26,6 +26,33 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// A second stream (default priority) forked from and joined back into the caller's stream with
+// events, used to run a long, throughput-bound update next to a chain of short, latency-bound
+// kernels.  Host objects only; created and destroyed inside one call.
+struct AuxStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t* ev = nullptr;
+  int nev = 0;
+  bool ok = false;
+  explicit AuxStream(int n_events) {
+    if (hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) != hipSuccess) {
+      stream = nullptr;
+      return;
+    }
+    ev = new hipEvent_t[n_events > 0 ? n_events : 1];
+    for (nev = 0; nev < n_events; ++nev)
+      if (hipEventCreateWithFlags(&ev[nev], hipEventDisableTiming) != hipSuccess) return;
+    ok = true;
+  }
+  ~AuxStream() {
+    for (int i = 0; i < nev; ++i) (void)hipEventDestroy(ev[i]);
+    delete[] ev;
+    if (stream) (void)hipStreamDestroy(stream);
+  }
+  AuxStream(const AuxStream&) = delete;
+  AuxStream& operator=(const AuxStream&) = delete;
+};
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- internal entry points shared between translation units -------------------------------

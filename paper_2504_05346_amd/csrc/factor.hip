@@ -312,7 +312,15 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   // step only reaches the columns of that outer block (narrow, K = NB); everything to the right
   // gets one update per outer block with K = kOuter*NB, which reads and writes the trailing
   // matrix kOuter times less often and runs the matrix cores on long reductions.
+  // That wide update is split in two: the column strip of the NEXT outer block stays on the
+  // caller's stream (the next diagonal block needs it), the rest runs on a second stream next
+  // to the latency-bound diagonal / panel chain of the next outer block.  Column ranges of the
+  // two streams are disjoint until the next strip, which waits for the previous rest.
   constexpr int kOuter = 4;
+  const int n_outer = (nb + kOuter - 1) / kOuter;
+  AuxStream aux(2 * n_outer);
+  if (!aux.ok) return THANOS_ERR_HIP;
+  int pending_join = -1;  // event index recorded on the aux stream after the last "rest"
   for (int k = 0; k < nb; ++k) {
     hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, s, Ap, Linv, bp, k, b, info);
     THANOS_LAUNCH_CHECK();
@@ -324,7 +332,8 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
     thanos_status st = gemm_f32(s, false, false, rem, NB, NB, 1.f, panel, bp, dinv, bp, 0.f,
                                 panel, bp, false);
     if (st != THANOS_OK) return st;
-    const int ob_begin = (k / kOuter) * kOuter;
+    const int ob = k / kOuter;
+    const int ob_begin = ob * kOuter;
     const int ob_end = std::min(nb, ob_begin + kOuter);
     // narrow: A_ij -= L_ik L_jk^T for block columns k < j < ob_end, lower tiles
     const int64_t ncols = (int64_t)(ob_end - (k + 1)) * NB;
@@ -334,16 +343,38 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
                     true);
       if (st != THANOS_OK) return st;
     }
-    // wide: after the last step of an outer block, everything right of it in one product
+    // wide: after the last step of an outer block, everything right of it
     if (k + 1 == ob_end && ob_end < nb) {
-      const int64_t rest = bp - (int64_t)ob_end * NB;
+      const int next_end = std::min(nb, ob_end + kOuter);
       const int64_t kk = (int64_t)(ob_end - ob_begin) * NB;
       const float* lp = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_begin * NB;
-      float* trail = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_end * NB;
-      st = gemm_f32(s, false, false, rest, rest, kk, -1.f, lp, bp, lp, bp, 1.f, trail, bp, true);
-      if (st != THANOS_OK) return st;
+      // fork: the rest (rows and columns >= next_end) on the second stream
+      if (next_end < nb) {
+        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * ob], s));
+        THANOS_HIP_CHECK(hipStreamWaitEvent(aux.stream, aux.ev[2 * ob], 0));
+        const int64_t rest = bp - (int64_t)next_end * NB;
+        const float* lr = lp + ((int64_t)(next_end - ob_end) * NB) * bp;
+        float* cr = Ap + ((int64_t)next_end * NB) * bp + (int64_t)next_end * NB;
+        st = gemm_f32(aux.stream, false, false, rest, rest, kk, -1.f, lr, bp, lr, bp, 1.f, cr, bp,
+                      true);
+        if (st != THANOS_OK) return st;
+      }
+      // the strip of the next outer block: it was last written by the previous rest
+      if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
+      {
+        const int64_t rows = bp - (int64_t)ob_end * NB;
+        const int64_t cols = (int64_t)(next_end - ob_end) * NB;
+        float* cs = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_end * NB;
+        st = gemm_f32(s, false, false, rows, cols, kk, -1.f, lp, bp, lp, bp, 1.f, cs, bp, true);
+        if (st != THANOS_OK) return st;
+      }
+      if (next_end < nb) {
+        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * ob + 1], aux.stream));
+        pending_join = 2 * ob + 1;
+      }
     }
   }
+  if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
 
   for (int S = 1; S < nb; S *= 2) {
     TrinvArgs a{Ap, Linv, Tb, bp, nb, S};

@@ -796,7 +796,7 @@ constexpr int kSuper = 8;
 size_t sweep_workspace_bytes(int64_t c, int64_t b, int B) {
   size_t n = 0;
   n += align_up((size_t)b * 4, 256);            // sx
-  n += align_up((size_t)c * B * kSuper * 4, 256);  // Lam
+  n += align_up((size_t)c * B * kSuper * 4 * 2, 256);  // Lam, two super-block buffers
   n += align_up((size_t)b * b * 4, 256);        // P
   n += align_up(2048 * 4, 256);                 // hist
   n += align_up(sizeof(SelState), 256);         // state
@@ -808,7 +808,7 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B) {
   char* p = reinterpret_cast<char*>(ws);
   SweepWs w;
   w.sx = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
-  w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * kSuper * 4));
+  w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * kSuper * 4 * 2));
   w.P = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
   w.hist = reinterpret_cast<unsigned int*>(carve(p, 2048 * 4));
   w.st = reinterpret_cast<SelState*>(carve(p, sizeof(SelState)));
@@ -878,12 +878,22 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   const unsigned rows4 = (unsigned)ceil_div(c, 4);
   const int super = unstructured ? 1 : kSuper;   // the global residual mask needs current weights
   const int ldl = B * super;
+  // The update that reaches right of a super-block is split like the wide update of the
+  // factorisation: the columns of the next super-block on the caller's stream, the rest on a
+  // second stream next to the (latency-bound) blocks of the next super-block.  The multipliers
+  // of consecutive super-blocks alternate between two buffers.
+  const int n_super = (int)ceil_div(b, (int64_t)B * super);
+  AuxStream aux(super > 1 ? 2 * n_super : 0);
+  if (super > 1 && !aux.ok) return THANOS_ERR_HIP;
+  int pending_join = -1;
   for (int64_t j1 = 0; j1 < b; j1 += B) {
     const int bw = (int)std::min<int64_t>(B, b - j1);
     const int64_t blk = j1 / B;
-    const int64_t sb_start = (blk / super) * super * (int64_t)B;
-    const int64_t sb_end = std::min<int64_t>(b, sb_start + (int64_t)super * B);
-    const int64_t loff = j1 - sb_start;  // column of this block inside the multiplier buffer
+    const int64_t sbi = blk / super;
+    const int64_t sb_start = sbi * super * (int64_t)B;
+    const int64_t sb_end = (super == 1) ? b : std::min<int64_t>(b, sb_start + (int64_t)super * B);
+    const int64_t loff = (super == 1) ? 0 : (j1 - sb_start);
+    float* lam_sb = w.Lam + (sbi & 1) * (int64_t)c * ldl;
     if (unstructured) {
       hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(1), 0, s, w.st);
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
@@ -906,7 +916,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.sx = w.sx;
     sa.mask_in = o->mask_in;
     sa.mask_out = mask;
-    sa.Lam = w.Lam + loff;
+    sa.Lam = lam_sb + loff;
     sa.st = w.st;
     sa.st_rw = w.st;
     sa.row_eq = w.row_eq;
@@ -928,20 +938,39 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     THANOS_LAUNCH_CHECK();
 
     {  // this block's update, up to the end of its super-block
-      UpdateArgs ua{W, w.Lam + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
+      UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
                     (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
       dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
       hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
       THANOS_LAUNCH_CHECK();
     }
-    if (j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block, right of it
-      UpdateArgs ua{W, w.Lam, w.P, mask, c, b, sb_start, sb_end, b, 0, 0,
-                    (int)(sb_end - sb_start), ldl, (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
-      dim3 grid((unsigned)ceil_div(b - sb_end, kTN), (unsigned)ceil_div(c, kTM));
-      hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
-      THANOS_LAUNCH_CHECK();
+    if (super > 1 && j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block
+      const int64_t next_end = std::min<int64_t>(b, sb_end + (int64_t)super * B);
+      const int kk = (int)(sb_end - sb_start);
+      if (next_end < b) {  // rest: right of the next super-block, second stream
+        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * sbi], s));
+        THANOS_HIP_CHECK(hipStreamWaitEvent(aux.stream, aux.ev[2 * sbi], 0));
+        UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+        dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
+        hipLaunchKernelGGL(k_update, grid, dim3(256), 0, aux.stream, ua);
+        THANOS_LAUNCH_CHECK();
+      }
+      if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
+      {  // strip: the columns of the next super-block
+        UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+        dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
+        hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
+        THANOS_LAUNCH_CHECK();
+      }
+      if (next_end < b) {
+        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * sbi + 1], aux.stream));
+        pending_join = (int)(2 * sbi + 1);
+      }
     }
   }
+  if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
 
   if (W_cast) {
     if (wdt == THANOS_F32)
