@@ -24,9 +24,14 @@ if ROOT not in sys.path:
 PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16/bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel (k_syrk16) from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs, scaled by a copy kernel of known size; None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes that crossed the L2 <-> fabric boundary per launch of the dominant kernel
+# (k_syrk16_dma), from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) of
+# `bench.py --steps 1 --warmup 0 --no-cpu-baseline --copy-probe`, each scaled by what the same
+# counter reads for the 1 GiB copy of --copy-probe (factors 2.0 and 1.0, i.e. the counters tick
+# in 2 KiB and 1 KiB).  See profiles/k_syrk16_dma_4096x11008_traffic.md.  Key: (c, b, T, calls).
+MEASURED_TRAFFIC_BYTES = {
+    (4096, 11008, 262144, 1): 41489086 * 2 * 1024 + 236844 * 1024,
+}
 
 
 def parse_args():
@@ -81,8 +86,8 @@ def cpu_baseline(args, W, X, torch):
         threads = max((p.get("num_threads", 1) for p in threadpool_info()), default=1)
     except Exception:  # pragma: no cover
         threads = os.cpu_count() or 1
-    tok_s = min(args.tokens, 2048)
-    rows_s = min(args.c, 16)
+    tok_s = min(args.tokens, 8192)
+    rows_s = min(args.c, 64)
     Xs = X[:tok_s].cpu().numpy()
     Ws = W[:rows_s].cpu().numpy()
     t0 = time.perf_counter()
@@ -184,7 +189,7 @@ def main():
         "phases_ms": {"hessian_accumulate": sum(acc_ms) / len(acc_ms),
                       "factor_and_sweep": sum(prune_ms) / len(prune_ms)},
         "kept_fraction": kept / (c * b),
-        "roofline": {"kernel": "k_syrk16 (thanos_hessian_accumulate)", "bound": "mfma",
+        "roofline": {"kernel": "k_syrk16_dma (thanos_hessian_accumulate)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_MFMA_F16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((c, b, T, args.chunks))},
