@@ -128,15 +128,31 @@ __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
   return __float_as_uint(fabsf(w) * sx);
 }
 
-// One wavefront per row; lanes stride over the residual columns.
+// One wavefront per row; lanes stride over the residual columns (16 bytes per lane when the
+// row segment is 16-byte aligned, so that a wavefront keeps 1 KB per load instruction in flight).
 // PASS 0: bin = key >> 21.  PASS 1: keys with key>>21 == prefix, bin = (key>>10) & 2047.
 // PASS 2: keys with key>>10 == prefix, bin = key & 1023; also counts those keys per row.
+template <int PASS>
+__device__ __forceinline__ void sel_count(unsigned int* h, unsigned int key, unsigned int prefix,
+                                          int& cand) {
+  if (PASS == 0) {
+    atomicAdd(&h[key >> 21], 1u);
+  } else if (PASS == 1) {
+    if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
+  } else {
+    if ((key >> 10) == prefix) {
+      atomicAdd(&h[key & 1023u], 1u);
+      ++cand;
+    }
+  }
+}
+
 template <int PASS>
 __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, int64_t c, int64_t b,
                                                   int64_t j1, const float* __restrict__ sx,
                                                   const SelState* __restrict__ st,
                                                   unsigned int* __restrict__ hist,
-                                                  int* __restrict__ row_cand) {
+                                                  int* __restrict__ row_cand, int vec) {
   __shared__ unsigned int h[2048];
   if (st->none) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -147,18 +163,22 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
   if (i < c) {
     const float* row = W + i * b;
     int cand = 0;
-    for (int64_t j = j1 + lane; j < b; j += 64) {
-      const unsigned int key = metric_key(row[j], sx[j]);
-      if (PASS == 0) {
-        atomicAdd(&h[key >> 21], 1u);
-      } else if (PASS == 1) {
-        if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
-      } else {
-        if ((key >> 10) == prefix) {
-          atomicAdd(&h[key & 1023u], 1u);
-          ++cand;
-        }
+    if (vec) {
+      const int64_t nvec = (b - j1) >> 2;
+      for (int64_t v = lane; v < nvec; v += 64) {
+        const int64_t j = j1 + 4 * v;
+        const float4 w4 = *reinterpret_cast<const float4*>(row + j);
+        const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
+        sel_count<PASS>(h, metric_key(w4.x, s4.x), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.y, s4.y), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.z, s4.z), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.w, s4.w), prefix, cand);
       }
+      for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64)
+        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, cand);
+    } else {
+      for (int64_t j = j1 + lane; j < b; j += 64)
+        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, cand);
     }
     if (PASS == 2) {
       for (int off = 32; off > 0; off >>= 1) cand += __shfl_down(cand, off, 64);
@@ -170,8 +190,6 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
     if (h[e]) atomicAdd(&hist[e], h[e]);
 }
 
-// Single workgroup: locate the bin that contains the wanted rank, fold it into the prefix,
-// clear the histogram for the next pass.
 // Start of a block: r <- r - ||M||_F^2 of the previous block (Alg. 1), reset the search.
 __global__ void k_sel_begin(SelState* __restrict__ st) {
   st->r_rem -= st->blk_count;
@@ -236,7 +254,7 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
                                                   int64_t j1, const float* __restrict__ sx,
                                                   const SelState* __restrict__ st,
                                                   const int* __restrict__ row_cand,
-                                                  int* __restrict__ row_eq) {
+                                                  int* __restrict__ row_eq, int vec) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave;
   if (i >= c) return;
@@ -247,7 +265,20 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
   const unsigned int tau = st->tau;
   const float* row = W + i * b;
   int n = 0;
-  for (int64_t j = j1 + lane; j < b; j += 64) n += (metric_key(row[j], sx[j]) == tau) ? 1 : 0;
+  if (vec) {
+    const int64_t nvec = (b - j1) >> 2;
+    for (int64_t v = lane; v < nvec; v += 64) {
+      const int64_t j = j1 + 4 * v;
+      const float4 w4 = *reinterpret_cast<const float4*>(row + j);
+      const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
+      n += (metric_key(w4.x, s4.x) == tau) + (metric_key(w4.y, s4.y) == tau) +
+           (metric_key(w4.z, s4.z) == tau) + (metric_key(w4.w, s4.w) == tau);
+    }
+    for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64)
+      n += (metric_key(row[j], sx[j]) == tau) ? 1 : 0;
+  } else {
+    for (int64_t j = j1 + lane; j < b; j += 64) n += (metric_key(row[j], sx[j]) == tau) ? 1 : 0;
+  }
   for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off, 64);
   if (lane == 0) row_eq[i] = n;
 }
@@ -895,18 +926,21 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     const int64_t loff = (super == 1) ? 0 : (j1 - sb_start);
     float* lam_sb = w.Lam + (sbi & 1) * (int64_t)c * ldl;
     if (unstructured) {
+      // 16-byte loads need W + i*b + j1 and sx + j1 aligned (W, sx come 256-byte aligned)
+      const int sel_vec = (b % 4 == 0 && j1 % 4 == 0 &&
+                           reinterpret_cast<uintptr_t>(W) % 16 == 0) ? 1 : 0;
       hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(1), 0, s, w.st);
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.hist, w.row_cand);
+                         w.hist, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_sel_scan<0>, dim3(1), dim3(256), 0, s, w.st, w.hist);
       hipLaunchKernelGGL(k_sel_hist<1>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.hist, w.row_cand);
+                         w.hist, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_sel_scan<1>, dim3(1), dim3(256), 0, s, w.st, w.hist);
       hipLaunchKernelGGL(k_sel_hist<2>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.hist, w.row_cand);
+                         w.hist, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_sel_scan<2>, dim3(1), dim3(256), 0, s, w.st, w.hist);
       hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.row_cand, w.row_eq);
+                         w.row_cand, w.row_eq, sel_vec);
       hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c);
       THANOS_LAUNCH_CHECK();
     }
