@@ -14,7 +14,9 @@
  *   - Every data pointer is a DEVICE pointer unless it says "host".  The caller owns all
  *     buffers; the library allocates no device memory and keeps no state between calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
- *     enqueued asynchronously on it; nothing synchronises with the host.
+ *     enqueued asynchronously on it; nothing synchronises with the host.  thanos_factor and
+ *     thanos_prune_layer also create one short-lived helper stream (default priority) per call,
+ *     forked from and joined back into `stream` with events; it is destroyed before they return.
  *   - The return value covers argument checks and launch errors only.  Numerical failure
  *     (a non-positive pivot) is reported through the device word `info_dev`, which the
  *     caller reads after synchronising the stream.
@@ -51,7 +53,7 @@ typedef struct {
                          means 6/10.  Ignored for THANOS_NM.                                  */
   int32_t n, m;       /* THANOS_NM: n of every m consecutive weights of a row are removed;
                          0 < n < m <= 16, m divides block_size and b                          */
-  int32_t block_size; /* B: columns pruned per sweep step, 1 <= B <= 128; last block may be
+  int32_t block_size; /* B: columns pruned per sweep step, 1 <= B <= 256; last block may be
                          narrower (unstructured only)                                         */
   float damping;      /* H_d = H + damping * mean(diag H) * I (relative damping, >= 0)        */
   const uint8_t* mask_in;  /* optional c*b device mask that replaces the selection step
@@ -109,10 +111,12 @@ size_t thanos_factor_workspace_bytes(int64_t b);
  * W_in: c*b of type wdt, ld = b, never modified.  H: b*b fp32 lower triangle (ignored when
  * opts->factor_in is given).  W_out: c*b fp32.  W_out_cast: NULL, or c*b of type wdt receiving
  * W_out rounded to nearest-even.  mask_out: c*b uint8, 1 = removed.  ws:
- * thanos_prune_workspace_bytes(c, b, opts) bytes.  info_dev: as in thanos_factor.
+ * thanos_prune_workspace_bytes(c, b, opts) bytes.  info_dev: as in thanos_factor; in addition
+ * it is set to -(i+1) if the system of row i met a non-positive pivot (that row's update is
+ * then meaningless; other rows are unaffected).
  * Ties in the metric are broken by ascending (row, column).
  * Errors: INVALID_ARG (NULL, sizes, n/m/B constraints, p outside [0,1)), UNSUPPORTED
- * (block_size > 128, m > 16), WORKSPACE, HIP.
+ * (block_size > 256, m > 16), WORKSPACE, HIP.
  */
 thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                                  const float* H, const thanos_prune_opts* opts /* host */,

@@ -41,7 +41,7 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
     if (o->m > 16) return THANOS_ERR_UNSUPPORTED;
   }
   if (o->factor_in && !o->xnorm2_in) return THANOS_ERR_INVALID_ARG;
-  if (o->block_size > 128) return THANOS_ERR_UNSUPPORTED;
+  if (o->block_size > 256) return THANOS_ERR_UNSUPPORTED;
   (void)c;
   return THANOS_OK;
 }

@@ -90,13 +90,15 @@ __global__ __launch_bounds__(256) void k_block_rows(BlockRowsArgs a) {
   const int64_t j1 = (int64_t)blockIdx.y * a.B;
   const int bw = (int)min((int64_t)a.B, a.b - j1);
   const int64_t col0 = j1 + (int64_t)blockIdx.x * kTN;
-  if (col0 >= a.b) return;
+  const int mrow0 = (int)blockIdx.z * kTM;  // row tile inside the block (B may exceed 128)
+  if (col0 >= a.b || mrow0 >= bw) return;
   const int n_ext = (int)min((int64_t)kTN, a.b - col0);
-  const float* A = a.U + j1 * a.b + j1;     // (m,k) at A[k*b + m]
-  const float* Bm = a.U + j1 * a.b + col0;  // (k,n) at B[k*b + n]
+  const int m_ext = min(kTM, bw - mrow0);
+  const float* A = a.U + j1 * a.b + j1 + mrow0;  // (m,k) at A[k*b + m]
+  const float* Bm = a.U + j1 * a.b + col0;       // (k,n) at B[k*b + n]
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<true, true>(acc, sm, A, a.b, bw, Bm, a.b, n_ext, 0, bw, a.vec, a.vec);
+  gemm_tile<true, true>(acc, sm, A, a.b, m_ext, Bm, a.b, n_ext, 0, bw, a.vec, a.vec);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
   for (int f = 0; f < 2; ++f)
@@ -106,7 +108,8 @@ __global__ __launch_bounds__(256) void k_block_rows(BlockRowsArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = acc_row(wm, f, r, lane);
-        if (row < bw && col < n_ext) a.P[(j1 + row) * a.b + col0 + col] = acc.v[f][g][r];
+        if (row < m_ext && col < n_ext)
+          a.P[(j1 + mrow0 + row) * a.b + col0 + col] = acc.v[f][g][r];
       }
     }
 }
@@ -579,30 +582,31 @@ __global__ __launch_bounds__(64 * WPB, (RPL == 1 ? 2 : 1)) void k_solve(SolveArg
 }
 
 // ------------------------------------------------------------------------------------------
-// Mask + per-row solve for systems of up to 128 unknowns: one workgroup of 128 threads (two
-// wavefronts) per row of W, thread t <-> block column t <-> row t of R_hat (128 registers).
+// Mask + per-row solve for systems of up to SMAX = 128 or 256 unknowns: one workgroup of SMAX
+// threads (2 or 4 wavefronts) per row of W, thread t <-> block column t <-> row t of R_hat
+// (SMAX registers).
 // Same symmetric Gauss-Jordan elimination and register renaming by panels of 4 as k_solve, in
 // its square-root-free form  A[rho][j] -= (A[rho][k] / d) * A[j][k],  so that the broadcast
 // column needs no scaling.  The pivot column travels through LDS (one barrier per pivot).
 // Only the registers that still hold live columns (j < s - 4*panel) are touched, in chunks of
 // 16, so a system of s unknowns costs ~s^2/2 fused multiply-adds per thread, not s*128.
-template <int SEL>
-__global__ __launch_bounds__(128, 3) void k_solve_wide(SolveArgs a) {
-  constexpr int SMAX = 128;
+template <int SEL, int SMAX>
+__global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(SolveArgs a) {
+  constexpr int NWV = SMAX / 64;
   __shared__ __attribute__((aligned(16))) float col[2][4][SMAX + 32];  // tail stays zero
   __shared__ float ukb[2][4];
   __shared__ float wrow[SMAX];
   __shared__ float key[SMAX];
   __shared__ int q[SMAX];
-  __shared__ int cnt[2];
-  __shared__ int eqc[2];
+  __shared__ int cnt[NWV];
+  __shared__ int eqc[NWV];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t i = blockIdx.x;
   const float* wrow_g = a.W + i * a.b + a.j1;
 
   const float w = (tid < a.bw) ? wrow_g[tid] : 0.f;
   wrow[tid] = w;
-  for (int e = tid; e < 2 * 4 * (SMAX + 32); e += 128) (&col[0][0][0])[e] = 0.f;
+  for (int e = tid; e < 2 * 4 * (SMAX + 32); e += SMAX) (&col[0][0][0])[e] = 0.f;
   bool sel = false;
   if (SEL == SEL_GIVEN) {
     sel = (tid < a.bw) && a.mask_in[i * a.b + a.j1 + tid] != 0;
@@ -630,15 +634,21 @@ __global__ __launch_bounds__(128, 3) void k_solve_wide(SolveArgs a) {
     const unsigned long long eqb = __ballot(eq);
     if (lane == 0) eqc[wave] = __popcll(eqb);
     __syncthreads();
-    const long long my = (long long)a.row_eq[i] + (wave ? eqc[0] : 0) +
+    int eq_before = 0;
+    for (int v = 0; v < wave; ++v) eq_before += eqc[v];
+    const long long my = (long long)a.row_eq[i] + eq_before +
                          __popcll(eqb & ((1ull << lane) - 1ull));
     sel = lt || (eq && my < need_eq);
   }
   const unsigned long long bal = __ballot(sel);
   if (lane == 0) cnt[wave] = __popcll(bal);
   __syncthreads();
-  const int s = cnt[0] + cnt[1];
-  const int myrank = (wave ? cnt[0] : 0) + __popcll(bal & ((1ull << lane) - 1ull));
+  int s = 0, sel_before = 0;
+  for (int v = 0; v < NWV; ++v) {
+    if (v < wave) sel_before += cnt[v];
+    s += cnt[v];
+  }
+  const int myrank = sel_before + __popcll(bal & ((1ull << lane) - 1ull));
   if (sel) q[myrank] = tid;
   if (tid < a.bw) a.mask_out[i * a.b + a.j1 + tid] = sel ? 1 : 0;
   if (SEL == SEL_THRESHOLD) {
@@ -865,8 +875,10 @@ static void launch_solve(hipStream_t s, const SolveArgs& a, int smax) {
     hipLaunchKernelGGL((k_solve<1, 1, SEL, 4>), dim3((unsigned)ceil_div(a.c, 4)), dim3(256), 0, s, a);
   } else if (smax <= 64) {
     hipLaunchKernelGGL((k_solve<2, 1, SEL, 4>), dim3((unsigned)ceil_div(a.c, 4)), dim3(256), 0, s, a);
+  } else if (a.bw <= 128) {
+    hipLaunchKernelGGL((k_solve_wide<SEL, 128>), dim3((unsigned)a.c), dim3(128), 0, s, a);
   } else {
-    hipLaunchKernelGGL((k_solve_wide<SEL>), dim3((unsigned)a.c), dim3(128), 0, s, a);
+    hipLaunchKernelGGL((k_solve_wide<SEL, 256>), dim3((unsigned)a.c), dim3(256), 0, s, a);
   }
 }
 
@@ -894,7 +906,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   {
     BlockRowsArgs a{U, w.P, b, B,
                     (aligned_b && reinterpret_cast<uintptr_t>(U) % 16 == 0) ? 1 : 0};
-    dim3 grid((unsigned)ceil_div(b, kTN), (unsigned)ceil_div(b, B));
+    dim3 grid((unsigned)ceil_div(b, kTN), (unsigned)ceil_div(b, B), (unsigned)ceil_div(B, kTM));
     hipLaunchKernelGGL(k_block_rows, grid, dim3(256), 0, s, a);
     THANOS_LAUNCH_CHECK();
   }

@@ -51,9 +51,9 @@ def test_host_side_argument_checks(L):
                                 None, None, 0, None, None) == 1
     bad = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=126, damping=0.01)
     assert t.thanos_prune_workspace_bytes(64, 256, bad) == 0          # m does not divide B
-    big = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=256,
+    big = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=512,
                       damping=0.01)
-    assert t.thanos_prune_workspace_bytes(64, 256, big) == 0          # B > 128 unsupported
+    assert t.thanos_prune_workspace_bytes(64, 256, big) == 0          # B > 256 unsupported
     assert t.thanos_factor_workspace_bytes(1000) >= 3 * 1024 * 1024 * 4
     p1 = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=1.0, n=0, m=0, block_size=128,
                      damping=0.01)

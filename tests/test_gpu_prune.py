@@ -92,6 +92,9 @@ def test_cfg1_nm(n, m, rho):
     (67, 200, 32, "nm"),
     (130, 260, 100, "unstructured"),    # B not a power of two
     (50, 150, 50, "unstructured"),      # B and b not multiples of 4: scalar load paths
+    (96, 768, 256, "unstructured"),     # block size 256 (configuration 5), 4 wavefronts per row
+    (64, 640, 256, "nm"),               # last block 128 wide
+    (40, 450, 200, "unstructured"),     # wide block, nothing aligned
     (9, 40, 128, "unstructured"),       # single narrow block
     (5, 16, 1, "unstructured"),         # B = 1
 ])
@@ -109,6 +112,35 @@ def test_ragged_shapes(c, b, B, mode):
         Wo, Mo = orc.prune_nm(W, H, 2, 4, B, 0.01)
     assert info == 0
     _check(W, H32, Wg, Mg, Wo, Mo)
+
+
+def test_cfg5_like_block256_heavy_tailed():
+    # configuration 5 in small: N(0, 0.015^2) fp16 weights, outlier channels, 60 % unstructured,
+    # block 256
+    from tests.gpu_util import gpu_prune
+    spec = LayerSpec("t", c=160, b=1024, tokens=4096, dtype="f16", w_std=0.015, rho=0.7, k_mix=16,
+                     seed=11, outliers=True)
+    W, X = make_weight(spec), make_calibration(spec)
+    H32 = orc.hessian(X).astype(np.float32)
+    H = H32.astype(np.float64)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.6, B=256)
+    assert info == 0
+    assert int(Mg.sum()) == orc.num_to_remove(0.6, 160, 1024)
+    Wo, Mo = orc.prune_fast(W, H, mode="unstructured", p=0.6, B=256, damp=0.01)
+    assert (Mg != Mo).mean() < 1e-4
+    Wt, _ = orc.prune_fast(W, H, mode="unstructured", p=0.6, B=256, damp=0.01, mask_in=Mg)
+    assert _rel(Wg, Wt) < 1e-3
+    eo = orc.reconstruction_error(W, Wo, H)
+    eg = orc.reconstruction_error(W, Wg.astype(np.float64), H)
+    assert abs(eg - eo) <= 0.01 * eo
+    # 4:8 at block 256: s = 128 per row
+    Wg, Mg, info = gpu_prune(W, H32, mode="nm", n=4, m=8, B=256)
+    assert info == 0
+    assert np.all(Mg.reshape(160, 128, 8).sum(axis=2) == 4)
+    Wt, _ = orc.prune_fast(W, H, mode="nm", n=4, m=8, B=256, damp=0.01, mask_in=Mg)
+    assert _rel(Wg, Wt) < 1e-3
+    _, Mo = orc.prune_fast(W, H, mode="nm", n=4, m=8, B=256, damp=0.01)
+    assert (Mg != Mo).mean() < 1e-3
 
 
 # --------------------------------------------------------------------------- forced masks
