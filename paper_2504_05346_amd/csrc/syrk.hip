@@ -19,8 +19,9 @@
 //     s fetches 8 bytes of row (s / 4), channels 4 (s % 4)..+3, and receives the four rows of
 //     ONE channel, i.e. four consecutive reduction values; two such reads make an operand.
 //     The 64-byte row padding spreads the four rows of a read over all 64 banks.
-//   * one barrier per k-step: wait for the own loads of this step (vmcnt), barrier, issue the
-//     loads three steps ahead into the stage that was consumed last, multiply.
+//   * one barrier per k-step: wait for the own loads of the next step (vmcnt), barrier, then
+//     multiply with the operand reads of the following slice and the loads four steps ahead
+//     (into the stage that was consumed last) interleaved one by one between the MFMAs.
 // Fallback kernel (k_syrk16; any alignment, any b): 8x8 patches are loaded with guarded scalar
 // loads, transposed in registers (v_perm_b32) and written to LDS already k-packed; fragment f
 // of a panel is the channel set {8x + f}, which keeps both LDS directions conflict-free.
@@ -291,10 +292,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
 
   const int64_t nkt = (a.n_tok + kDmaKT - 1) / kDmaKT;
 
-  // Issue the row loads of this wavefront for k-step kt.  Steps past the end get an empty
-  // descriptor: every lane is out of range, nothing is read and zeros are written, so the wait
-  // counts below stay uniform.
-  auto issue = [&](int64_t kt) {
+  // Descriptor and LDS destination of this wavefront's row loads of k-step kt (scalar
+  // registers).  Steps past the end get an empty descriptor: every lane is out of range, nothing
+  // is read and zeros are written, so the wait counts below stay uniform.
+  auto prep = [&](int64_t kt, u32x4& rs, uint32_t& dst) {
     const int64_t t0 = kt * kDmaKT + RPW * wave;
     int64_t rem_bytes = ((a.n_tok - t0 - 1) * a.ldx + a.b) * 2;
     const uint16_t* base = a.X + t0 * a.ldx;
@@ -304,42 +305,45 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
     }
     const uint32_t nrec = rem_bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)rem_bytes;
     const uint64_t ba = reinterpret_cast<uint64_t>(base);
-    u32x4 rs;
     rs.x = __builtin_amdgcn_readfirstlane((uint32_t)ba);
     rs.y = __builtin_amdgcn_readfirstlane((uint32_t)(ba >> 32) & 0xffffu);  // stride 0
     rs.z = __builtin_amdgcn_readfirstlane(nrec);
     rs.w = 0x00020000u;
-    const uint32_t dst = lds_base + (uint32_t)((int)(kt % kDmaStages) * kDmaStageBytes +
-                                               (RPW * wave) * kDmaRow);
-    const uint32_t row_bytes = __builtin_amdgcn_readfirstlane((uint32_t)(a.ldx * 2));
-#pragma unroll
-    for (int r = 0; r < RPW; ++r)
-      dma_row(rs, __builtin_amdgcn_readfirstlane(dst + r * kDmaRow), voff, r * row_bytes);
+    dst = __builtin_amdgcn_readfirstlane(
+        lds_base + (uint32_t)((int)(kt % kDmaStages) * kDmaStageBytes + (RPW * wave) * kDmaRow));
   };
-  auto read_frags = [&](int64_t kt, int ks, u32x4 (&af)[4], u32x4 (&bf)[GN]) {
-    const char* st = lds + (int)(kt % kDmaStages) * kDmaStageBytes + lane_off + ks * 16 * kDmaRow;
+  const uint32_t row_bytes = __builtin_amdgcn_readfirstlane((uint32_t)(a.ldx * 2));
+  auto issue = [&](int64_t kt) {
+    u32x4 rs;
+    uint32_t dst;
+    prep(kt, rs, dst);
 #pragma unroll
-    for (int f = 0; f < 4; ++f) af[f] = frag_read_tr(st, (32 * (4 * wm + f)) * 2);
-#pragma unroll
-    for (int g = 0; g < GN; ++g) bf[g] = frag_read_tr(st, 512 + (32 * (GN * wn + g)) * 2);
+    for (int r = 0; r < RPW; ++r) dma_row(rs, dst + r * kDmaRow, voff, r * row_bytes);
   };
-  auto mma = [&](const u32x4 (&af)[4], const u32x4 (&bf)[GN]) {
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int f = 0; f < 4; ++f)
-#pragma unroll
-      for (int g = 0; g < GN; ++g) acc[f][g] = mfma16<BF16>(af[f], bf[g], acc[f][g]);
-    __builtin_amdgcn_sched_barrier(0);
+  // Fragment k of a 16-token slice, in the order the MFMAs first need them:
+  // a0, b0 .. b(GN-1), a1, a2, a3.
+  auto read_item = [&](int k, const char* st, u32x4 (&af)[4], u32x4 (&bf)[GN]) {
+    if (k == 0) af[0] = frag_read_tr(st, (32 * (4 * wm)) * 2);
+    else if (k <= GN) bf[k - 1] = frag_read_tr(st, 512 + (32 * (GN * wn + k - 1)) * 2);
+    else af[k - GN] = frag_read_tr(st, (32 * (4 * wm + k - GN)) * 2);
   };
 
-  // Schedule per k-step kt (two 16-token slices):
-  //   read slice 1 of kt | MFMA slice 0 of kt | wait: own loads of kt+1 landed, own LDS reads
-  //   done | barrier | issue loads of kt+4 into the stage of kt | read slice 0 of kt+1 |
-  //   MFMA slice 1 of kt.
-  // Every MFMA group has its operands fetched one group earlier, and the barrier sits behind
-  // a group of queued MFMAs.  vmcnt(n): at most n of this wavefront's loads still pending.
+  // Schedule per k-step kt (two 16-token slices of NMF MFMAs each):
+  //   MFMAs of slice 0, with the fragment reads of slice 1 riding behind the first of them |
+  //   wait: own loads of kt+1 landed, own LDS reads done | barrier |
+  //   MFMAs of slice 1, with the fragment reads of slice 0 of kt+1 behind the first half and
+  //   the row loads of kt+4 (into the stage of kt) behind the second half.
+  // All wavefronts of a workgroup leave the barrier together, so anything issued in a bunch
+  // there would leave the matrix core idle on every SIMD at once; issued one or two at a time
+  // behind an MFMA (32 cycles each) they cost nothing.  The scheduling barriers pin that order.
+  // vmcnt(n): at most n of this wavefront's loads still pending.
   constexpr int kWaitPrologue = (RPW * 3 & 15) | ((RPW * 3 >> 4) << 14) | 0x0F70;  // 3 steps pending
   constexpr int kWaitLoop = (RPW * 2 & 15) | ((RPW * 2 >> 4) << 14) | 0x0070;      // 2 steps, lgkm 0
+  constexpr int NMF = 4 * GN;                      // MFMAs per slice
+  constexpr int NFR = 4 + GN;                      // operand fragments per slice
+  constexpr int SLOTS = NMF / 2;                   // MFMAs that carry fragment reads
+  constexpr int PER = (NFR + SLOTS - 1) / SLOTS;   // fragment reads behind each of them
+  static_assert(RPW <= NMF - SLOTS, "one row load behind each MFMA of the second half");
   issue(0);
   issue(1);
   issue(2);
@@ -347,15 +351,43 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
   __builtin_amdgcn_s_waitcnt(kWaitPrologue);
   __syncthreads();
   u32x4 a0[4], b0[GN], a1[4], b1[GN];
-  read_frags(0, 0, a0, b0);
+  {
+    const char* st = lds + lane_off;
+#pragma unroll
+    for (int k = 0; k < NFR; ++k) read_item(k, st, a0, b0);
+  }
   for (int64_t kt = 0; kt < nkt; ++kt) {
-    read_frags(kt, 1, a1, b1);
-    mma(a0, b0);
+    {
+      const char* st = lds + (int)(kt % kDmaStages) * kDmaStageBytes + lane_off + 16 * kDmaRow;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NMF; ++i) {
+        acc[i / GN][i % GN] = mfma16<BF16>(a0[i / GN], b0[i % GN], acc[i / GN][i % GN]);
+#pragma unroll
+        for (int k = i * PER; k < (i + 1) * PER; ++k)
+          if (k < NFR) read_item(k, st, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
     __builtin_amdgcn_s_waitcnt(kWaitLoop);
     __syncthreads();
-    issue(kt + 4);
-    read_frags(kt + 1, 0, a0, b0);
-    mma(a1, b1);
+    {
+      u32x4 rs;
+      uint32_t dst;
+      prep(kt + 4, rs, dst);
+      const char* st = lds + (int)((kt + 1) % kDmaStages) * kDmaStageBytes + lane_off;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NMF; ++i) {
+        acc[i / GN][i % GN] = mfma16<BF16>(a1[i / GN], b1[i % GN], acc[i / GN][i % GN]);
+#pragma unroll
+        for (int k = i * PER; k < (i + 1) * PER; ++k)
+          if (k < NFR) read_item(k, st, a0, b0);
+        if (i >= SLOTS && i - SLOTS < RPW)
+          dma_row(rs, dst + (i - SLOTS) * kDmaRow, voff, (i - SLOTS) * row_bytes);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0), lgkmcnt(0): drain the look-ahead
 
