@@ -84,140 +84,313 @@ __global__ __launch_bounds__(256) void k_reverse_pad(const float* __restrict__ H
 }
 
 // ------------------------------------------------------------------------------------------
-// Cholesky factor and inverse of one NB x NB diagonal block, one workgroup of 256 threads.
+// Cholesky factor and inverse of one NB x NB diagonal block, one workgroup of 4 wavefronts.
 //   in : lower triangle of A'[kb*NB .. , kb*NB ..]
 //   out: L_kk in the same place (lower triangle), Linv diagonal block = L_kk^{-1} (full
 //        square, zeros above the diagonal).
 //
-// In-place elimination on one array X held in REGISTERS, 8x8 elements per thread (thread
-// (bi, bj) owns rows 8bi.., columns 8bj..).  Before step k column j > k of X holds the
-// partially reduced A, afterwards (j <= k) it holds column j of the growing inverse T:
-//   l_i = X[i][k] / sqrt(d),  d = X[k][k]
-//   X[i][j] -= l_i * X[j][k]/sqrt(d)   (j > k: Cholesky update, symmetric source)
-//   X[i][j] -= l_i * X[k][j]/sqrt(d)   (j < k: the same row operation applied to T)
-//   X[i][k]  = -l_i / sqrt(d),  X[k][j<k] /= sqrt(d),  X[k][k] = 1/sqrt(d)
-// for rows i > k only.  Per step the owners of column k and of row k publish 128 values
-// through a double-buffered LDS vector (one barrier per step); everything else is register
-// arithmetic with static indices (the 8 steps of a block column are unrolled).
-__global__ __launch_bounds__(256) void k_chol_diag(float* __restrict__ Ap, float* __restrict__ Linv,
-                                                   int64_t bp, int kb_glob, int64_t b,
-                                                   int32_t* __restrict__ info) {
-  __shared__ __attribute__((aligned(16))) float buf[2][NB];
-  __shared__ float Lout[NB][NB + 1];
-  const int tid = threadIdx.x;
-  const int bi = tid >> 4, bj = tid & 15;
+// The block lives in LDS (S: A -> L, T: the inverse) and is processed in four steps of 32
+// columns.  Everything runs on the matrix cores, including the pivot loop:
+//
+//  * Pivot loop of step j (32 pivots, no barrier).  A 32x32 tile held in the accumulator
+//    layout of v_mfma_f32_32x32x2_f32 has row k in lanes (lo = column, hi = hk) of register rk.
+//    For a symmetric tile D that row is also column k, i.e. it is already laid out as BOTH
+//    operands of the rank-1 update D -= u u^T / d, u = D[k][:], d = u_k: one MFMA per pivot,
+//    no cross-lane traffic except the broadcast of d.  Column k of L is u / sqrt(d).
+//    Every wavefront keeps its own copy of the diagonal tile D and repeats that update, so
+//    that it can apply the same pivot to a second tile without talking to the others:
+//      wavefront 0     : T~ (starts as I), T~ -= (u/d) T~[k][:] for rows != k; after 32 pivots
+//                        T~ = L~^{-1} (unit lower), and L_jj^{-1} = diag(1/sqrt(d)) T~;
+//      wavefront w >= 1: the panel tile A_ij (i = j + w) held TRANSPOSED, so that its column k
+//                        is again row k of the register tile: A_ij^T -= u (A_ij[:,k] / d)^T;
+//                        column k of L_ij is A_ij[:,k] / sqrt(d).
+//  * Trailing update of the remaining lower tiles, A_il -= L_ij L_lj^T (i >= l > j), operands
+//    read from LDS.
+//  * After the four steps: the off-diagonal blocks of the inverse by recursive doubling over
+//    32- and 64-blocks, X21 = -T22 (L21 T11), with the strict upper tiles of S as scratch.
+constexpr int kCdLd = NB + 1;  // LDS row stride in floats: conflict-free rows and columns
+constexpr size_t kCholDiagSmem = (2 * (size_t)NB * kCdLd + 4 * 128) * sizeof(float);
+
+__device__ __forceinline__ int cd_row(int r, int hi) { return 8 * (r >> 2) + 4 * hi + (r & 3); }
+
+// acc += sign * A[0:32, 0:32] * B, A[m][k] at pa[m*kCdLd + k];
+// B_KN: B[k][n] at pb[k*kCdLd + n], else B given as rows of n: B[k][n] at pb[n*kCdLd + k].
+// All 32 operand values of a lane are fetched before the first MFMA.
+template <bool B_KN>
+__device__ __forceinline__ void cd_tile_mma32(f32x16& acc, const float* pa, const float* pb,
+                                              float sign, int lo, int hi) {
+  float av[16], bv[16];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    av[q] = pa[lo * kCdLd + 2 * q + hi];
+    bv[q] = B_KN ? pb[(2 * q + hi) * kCdLd + lo] : pb[lo * kCdLd + 2 * q + hi];
+  }
+#pragma unroll
+  for (int q = 0; q < 16; ++q)
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(sign * av[q], bv[q], acc, 0, 0, 0);
+}
+__device__ __forceinline__ void cd_tile_load(f32x16& acc, const float* p, int lo, int hi) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = p[cd_row(r, hi) * kCdLd + lo];
+}
+__device__ __forceinline__ void cd_tile_store(float* p, const f32x16& acc, float scale, int lo,
+                                              int hi) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) p[cd_row(r, hi) * kCdLd + lo] = scale * acc[r];
+}
+
+// The 32 pivots of one step for one wavefront.  ROLE 0: second tile is T~ (inverse of the
+// diagonal tile), ROLE 1: second tile is the transposed panel tile whose rows in S start at
+// `prow`.  `aux` points at this wavefront's 128 floats of LDS scratch.  Returns the first
+// non-positive pivot (or -1).
+//
+// A wavefront cannot overlap its own vector instructions with its own MFMAs, so the pivot loop
+// is kept to the bare chain: broadcast d, 1/d, the two operands, two MFMAs, one LDS write of
+// the UNSCALED column of L.  The scaling by 1/sqrt(d) is applied to the whole tile afterwards.
+template <int ROLE>
+__device__ __forceinline__ int cd_pivots(float* S, float* T, float* aux, int c0, int prow, int lo,
+                                         int hi) {
+  f32x16 D, E;
+  cd_tile_load(D, S + c0 * kCdLd + c0, lo, hi);
+  if (ROLE == 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) E[r] = (cd_row(r, hi) == lo) ? 1.f : 0.f;
+  } else {  // E[n][m] = A_ij[m][n]
+#pragma unroll
+    for (int r = 0; r < 16; ++r) E[r] = S[(prow + lo) * kCdLd + c0 + cd_row(r, hi)];
+  }
+  __syncthreads();  // every wavefront has its copy of D before L_jj overwrites it
+  float* ltile = S + (ROLE == 0 ? c0 : prow) * kCdLd + c0;  // the tile of L this wavefront writes
+  // key[h] = lo in the lanes that hold rows of half h (rows 4..7 mod 8 for h = 1), else -1:
+  // (key[hk] >= k) selects the lanes of row k with column >= k, (key[hk] >= 0) all of row k.
+  const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
+  // where column k of L goes: lane lo owns row lo of the tile; the other half writes to scratch
+  float* dst[2] = {hi == 0 ? ltile + lo * kCdLd : aux + 32 + lo,
+                   hi == 1 ? ltile + lo * kCdLd : aux + 32 + lo};
+  float dl = 1.f;  // pivot of column lo
+#pragma unroll
+  for (int k = 0; k < 32; ++k) {
+    const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(D[rk]), k + 32 * hk));
+    const float rd = __builtin_amdgcn_rcpf(d);
+    const float u = (key[hk] >= k) ? D[rk] : 0.f;  // row k = column k of the reduced tile
+    const float au = -rd * u;
+    D = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, D, 0, 0, 0);
+    dl = (lo == k) ? d : dl;
+    const float ek = (key[hk] >= 0) ? E[rk] : 0.f;  // ROLE 0: T~[k][:], ROLE 1: A_ij[:, k]
+    if (ROLE == 0) {
+      const float a2 = (lo == k) ? 0.f : au;  // row k itself stays
+      dst[hk][k] = u;                         // L_jj[:, k] * sqrt(d)
+      E = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, ek, E, 0, 0, 0);
+    } else {
+      dst[hk][k] = ek;                        // L_ij[:, k] * sqrt(d)
+      E = __builtin_amdgcn_mfma_f32_32x32x2f32(u, -rd * ek, E, 0, 0, 0);
+    }
+  }
+  // a non-positive pivot: report the first one (what was computed after it is garbage)
+  const unsigned long long badm = __ballot(!(dl > 0.f)) & 0xffffffffull;
+  const int bad = badm ? c0 + (__ffsll((long long)badm) - 1) : -1;
+  float isd = __builtin_amdgcn_rsqf(dl);
+  isd = fmaf(0.5f * isd, fmaf(-dl * isd, isd, 1.f), isd);
+  // columns of L: scale column lo by 1/sqrt(d_lo)
+  {
+    f32x16 C;
+    cd_tile_load(C, ltile, lo, hi);
+    cd_tile_store(ltile, C, isd, lo, hi);
+  }
+  if (ROLE == 0) {  // L_jj^{-1} = diag(1/sqrt(d)) T~
+    aux[lo] = isd;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      T[(c0 + cd_row(r, hi)) * kCdLd + c0 + lo] = E[r] * aux[cd_row(r, hi)];
+  }
+  return bad;
+}
+
+// Two wavefronts per SIMD at most: keeps the register budget at 256 so that the MFMA
+// accumulators stay in ordinary vector registers (they are read lane-wise every pivot).
+__global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
+                                                      float* __restrict__ Linv, int64_t bp,
+                                                      int kb_glob, int64_t b,
+                                                      int32_t* __restrict__ info) {
+  extern __shared__ __attribute__((aligned(16))) float cd_smem[];
+  float* S = cd_smem;
+  float* T = cd_smem + NB * kCdLd;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float* aux = cd_smem + 2 * NB * kCdLd + 128 * wave;  // per-wavefront scratch
+  const int lo = lane & 31, hi = lane >> 5;
   float* A = Ap + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
   float* Li = Linv + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
-  float X[8][8];
+#ifdef CD_DEBUG
+  long long tc[16], tr[16];
+  int nt = 0;
+#define CD_MARK() do { tc[nt] = clock64(); tr[nt] = wall_clock64(); ++nt; } while (0)
+#else
+#define CD_MARK() do {} while (0)
+#endif
+  CD_MARK();
+
+  // lower triangle -> S, mirrored inside the diagonal 32x32 tiles (the pivot loop wants them
+  // symmetric); the strict upper 32-tiles stay undefined (scratch).  The first 32 columns are
+  // stored right away; the loads of the other 96 columns are issued now and stored to LDS after
+  // the first pivot loop, which does not touch them.
+  auto put = [&](int i, int c4, const float4& v) {
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    if (c4 <= i) {
 #pragma unroll
-  for (int ii = 0; ii < 8; ++ii) {
-    const float4 a0 = *reinterpret_cast<const float4*>(A + (int64_t)(8 * bi + ii) * bp + 8 * bj);
-    const float4 a1 = *reinterpret_cast<const float4*>(A + (int64_t)(8 * bi + ii) * bp + 8 * bj + 4);
-    X[ii][0] = a0.x; X[ii][1] = a0.y; X[ii][2] = a0.z; X[ii][3] = a0.w;
-    X[ii][4] = a1.x; X[ii][5] = a1.y; X[ii][6] = a1.z; X[ii][7] = a1.w;
-  }
-  int badk = -1;
-  for (int kb = 0; kb < NB / 8; ++kb) {
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const int k = 8 * kb + kk;
-      float* bw = buf[k & 1];
-      // publish column k (rows >= k) and row k (columns < k): 8 consecutive entries per owner
-      if (bj == kb && bi == kb) {
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = (e < kk) ? X[kk][e] : X[e][kk];
-        *reinterpret_cast<float4*>(&bw[8 * kb]) = make_float4(v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4*>(&bw[8 * kb + 4]) = make_float4(v[4], v[5], v[6], v[7]);
-      } else if (bj == kb && bi > kb) {
-        *reinterpret_cast<float4*>(&bw[8 * bi]) =
-            make_float4(X[0][kk], X[1][kk], X[2][kk], X[3][kk]);
-        *reinterpret_cast<float4*>(&bw[8 * bi + 4]) =
-            make_float4(X[4][kk], X[5][kk], X[6][kk], X[7][kk]);
-      } else if (bi == kb && bj < kb) {
-        *reinterpret_cast<float4*>(&bw[8 * bj]) =
-            make_float4(X[kk][0], X[kk][1], X[kk][2], X[kk][3]);
-        *reinterpret_cast<float4*>(&bw[8 * bj + 4]) =
-            make_float4(X[kk][4], X[kk][5], X[kk][6], X[kk][7]);
-      }
-      __syncthreads();
-      float d = bw[k];
-      if (!(d > 0.f)) {
-        if (badk < 0) badk = k;
-        d = 1.f;
-      }
-      const float sd = sqrtf(d);
-      const float inv = 1.f / sd;
-      if (bi >= kb) {  // rows of earlier block rows are final
-        const float4 r0 = *reinterpret_cast<const float4*>(&bw[8 * bi]);
-        const float4 r1 = *reinterpret_cast<const float4*>(&bw[8 * bi + 4]);
-        const float4 c0 = *reinterpret_cast<const float4*>(&bw[8 * bj]);
-        const float4 c1 = *reinterpret_cast<const float4*>(&bw[8 * bj + 4]);
-        float li[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-        float vj[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-        const float s_hi = (bi > kb) ? inv : 0.f;  // rows of this thread with row <= k get 0
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          li[e] *= (e > kk) ? inv : s_hi;
-          vj[e] *= inv;
-        }
-        if (bi == kb) {  // row k becomes final: T[k][j<k] scaled, T[k][k] = 1/sqrt(d)
-          if (bj < kb) {
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) X[kk][jj] = vj[jj];
-          } else if (bj == kb) {
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-              if (jj < kk) X[kk][jj] = vj[jj];
-              else if (jj == kk) X[kk][jj] = inv;
-            }
-          }
-        }
-#pragma unroll
-        for (int ii = 0; ii < 8; ++ii)
-#pragma unroll
-          for (int jj = 0; jj < 8; ++jj) X[ii][jj] = fmaf(-li[ii], vj[jj], X[ii][jj]);
-        if (bj == kb) {  // column k: publish L[:, k], start column k of the inverse
-          if (bi > kb) {
-#pragma unroll
-            for (int ii = 0; ii < 8; ++ii) {
-              Lout[8 * bi + ii][k] = li[ii];
-              X[ii][kk] = -li[ii] * inv;
-            }
-          } else {
-#pragma unroll
-            for (int ii = 0; ii < 8; ++ii) {
-              if (ii > kk) {
-                Lout[8 * bi + ii][k] = li[ii];
-                X[ii][kk] = -li[ii] * inv;
-              } else if (ii == kk) {
-                Lout[8 * bi + ii][k] = sd;
-              }
-            }
-          }
+      for (int t = 0; t < 4; ++t) {
+        const int j = c4 + t;
+        if (j <= i) {
+          S[i * kCdLd + j] = vv[t];
+          if ((j >> 5) == (i >> 5)) S[j * kCdLd + i] = vv[t];
         }
       }
     }
+  };
+  constexpr int kVecA = NB * 8 / 256, kVecB = NB * 24 / 256;
+  float4 va[kVecA], vb[kVecB];
+#pragma unroll
+  for (int q = 0; q < kVecA; ++q) {
+    const int e = tid + 256 * q, i = e / 8, c4 = (e % 8) * 4;
+    va[q] = (c4 <= i) ? *reinterpret_cast<const float4*>(A + (int64_t)i * bp + c4)
+                      : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int q = 0; q < kVecB; ++q) {
+    const int e = tid + 256 * q, i = e / 24, c4 = 32 + (e % 24) * 4;
+    vb[q] = (c4 <= i) ? *reinterpret_cast<const float4*>(A + (int64_t)i * bp + c4)
+                      : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int q = 0; q < kVecA; ++q) {
+    const int e = tid + 256 * q;
+    put(e / 8, (e % 8) * 4, va[q]);
+  }
+  __syncthreads();
+  CD_MARK();
+
+  int badk = -1;
+  for (int j = 0; j < NB / 32; ++j) {
+    const int c0 = 32 * j;
+    const int ti = j + wave;  // panel tile row of wavefronts >= 1
+    if (wave == 0) {
+      const int bad = cd_pivots<0>(S, T, aux, c0, 0, lo, hi);
+      if (badk < 0) badk = bad;
+    } else if (ti < NB / 32) {
+      (void)cd_pivots<1>(S, T, aux, c0, 32 * ti, lo, hi);
+    } else {
+      __syncthreads();  // the barrier inside cd_pivots
+    }
+    if (j == 0) {
+#pragma unroll
+      for (int q = 0; q < kVecB; ++q) {
+        const int e = tid + 256 * q;
+        put(e / 24, 32 + (e % 24) * 4, vb[q]);
+      }
+    }
+    __syncthreads();
+    CD_MARK();
+    // trailing tiles (i, l), j < l <= i < 4, dealt round-robin to the wavefronts
+    {
+      int t = 0;
+      for (int i = j + 1; i < NB / 32; ++i)
+        for (int l = j + 1; l <= i; ++l, ++t) {
+          if ((t & 3) != wave) continue;
+          f32x16 C;
+          float* pc = S + (32 * i) * kCdLd + 32 * l;
+          cd_tile_load(C, pc, lo, hi);
+          cd_tile_mma32<false>(C, S + (32 * i) * kCdLd + c0, S + (32 * l) * kCdLd + c0, -1.f, lo,
+                               hi);
+          cd_tile_store(pc, C, 1.f, lo, hi);
+        }
+    }
+    __syncthreads();
+    CD_MARK();
   }
   if (badk >= 0 && tid == 0) {
     const int64_t orig = b - ((int64_t)kb_glob * NB + badk);  // 1-based original column
     atomicCAS(info, 0, (int32_t)(orig > 0 ? orig : 1));
   }
+
+  // inverse, 32 -> 64: pairs (0,1) and (2,3); scratch = strict upper tile (p, p+1) of S
+  if (wave < 2) {
+    const int p0 = 64 * wave, p1 = p0 + 32;
+    f32x16 C;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) C[r] = 0.f;
+    cd_tile_mma32<true>(C, S + p1 * kCdLd + p0, T + p0 * kCdLd + p0, 1.f, lo, hi);
+    float* w = S + p0 * kCdLd + p1;
+    cd_tile_store(w, C, 1.f, lo, hi);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) C[r] = 0.f;
+    cd_tile_mma32<true>(C, T + p1 * kCdLd + p1, w, 1.f, lo, hi);
+    cd_tile_store(T + p1 * kCdLd + p0, C, -1.f, lo, hi);
+  }
   __syncthreads();
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
-    if (j <= i) A[(int64_t)i * bp + j] = Lout[i][j];
-  }
+  CD_MARK();
+  // 64 -> 128: W = L[64:128, 0:64] T[0:64, 0:64] into S[0:64, 64:128], then
+  // T[64:128, 0:64] = -T[64:128, 64:128] W; one 32x32 tile per wavefront.
+  {
+    const int ti = wave >> 1, tj = wave & 1;  // tile inside the 64x64 block
+    f32x16 C;
 #pragma unroll
-  for (int ii = 0; ii < 8; ++ii) {
-    const int i = 8 * bi + ii;
-    float o[8];
+    for (int r = 0; r < 16; ++r) C[r] = 0.f;
+    // T[0:64,0:64] is lower triangular: 32-blocks of k from tj
+    for (int kb = tj; kb < 2; ++kb)
+      cd_tile_mma32<true>(C, S + (64 + 32 * ti) * kCdLd + 32 * kb,
+                          T + (32 * kb) * kCdLd + 32 * tj, 1.f, lo, hi);
+    cd_tile_store(S + (32 * ti) * kCdLd + 64 + 32 * tj, C, 1.f, lo, hi);
+    __syncthreads();
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) o[jj] = (8 * bj + jj <= i) ? X[ii][jj] : 0.f;
-    float* dst = Li + (int64_t)i * bp + 8 * bj;
-    *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
-    *reinterpret_cast<float4*>(dst + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    for (int r = 0; r < 16; ++r) C[r] = 0.f;
+    // T[64:128,64:128] is lower triangular: 32-blocks of k up to ti
+    for (int kb = 0; kb <= ti; ++kb)
+      cd_tile_mma32<true>(C, T + (64 + 32 * ti) * kCdLd + 64 + 32 * kb,
+                          S + (32 * kb) * kCdLd + 64 + 32 * tj, 1.f, lo, hi);
+    cd_tile_store(T + (64 + 32 * ti) * kCdLd + 32 * tj, C, -1.f, lo, hi);
   }
+  __syncthreads();
+  CD_MARK();
+  {
+    constexpr int kVec = NB * (NB / 4) / 256;
+    float4 l[kVec], t[kVec];
+#pragma unroll
+    for (int q = 0; q < kVec; ++q) {
+      const int e = tid + 256 * q, i = e / (NB / 4), c4 = (e % (NB / 4)) * 4;
+      float lv[4], tv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool low = c4 + u <= i;
+        lv[u] = low ? S[i * kCdLd + c4 + u] : 0.f;
+        tv[u] = low ? T[i * kCdLd + c4 + u] : 0.f;
+      }
+      l[q] = make_float4(lv[0], lv[1], lv[2], lv[3]);
+      t[q] = make_float4(tv[0], tv[1], tv[2], tv[3]);
+    }
+#pragma unroll
+    for (int q = 0; q < kVec; ++q) {
+      const int e = tid + 256 * q, i = e / (NB / 4), c4 = (e % (NB / 4)) * 4;
+      if (c4 + 3 <= i) {
+        *reinterpret_cast<float4*>(A + (int64_t)i * bp + c4) = l[q];
+      } else {
+        const float lv[4] = {l[q].x, l[q].y, l[q].z, l[q].w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (c4 + u <= i) A[(int64_t)i * bp + c4 + u] = lv[u];
+      }
+      *reinterpret_cast<float4*>(Li + (int64_t)i * bp + c4) = t[q];
+    }
+  }
+#ifdef CD_DEBUG
+  __syncthreads();
+  CD_MARK();
+  if (tid == 0)
+    for (int q = 1; q < nt; ++q) {
+      Li[2 * q] = (float)(tc[q] - tc[q - 1]);
+      Li[2 * q + 1] = (float)(tr[q] - tr[q - 1]);
+    }
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -316,13 +489,16 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   // caller's stream (the next diagonal block needs it), the rest runs on a second stream next
   // to the latency-bound diagonal / panel chain of the next outer block.  Column ranges of the
   // two streams are disjoint until the next strip, which waits for the previous rest.
+  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_chol_diag),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kCholDiagSmem));
   constexpr int kOuter = 4;
   const int n_outer = (nb + kOuter - 1) / kOuter;
   AuxStream aux(2 * n_outer);
   if (!aux.ok) return THANOS_ERR_HIP;
   int pending_join = -1;  // event index recorded on the aux stream after the last "rest"
   for (int k = 0; k < nb; ++k) {
-    hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, s, Ap, Linv, bp, k, b, info);
+    hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), kCholDiagSmem, s, Ap, Linv, bp, k, b, info);
     THANOS_LAUNCH_CHECK();
     const int64_t rem = bp - (int64_t)(k + 1) * NB;
     if (rem <= 0) break;
