@@ -73,6 +73,9 @@ typedef struct {
  *    the strict upper triangle may or may not have been written.  The caller zeroes H before
  *    the first chunk.  Xc: [n_tok, b] of type xdt, row stride ldx elements, never modified.
  *    Products are exact (fp16/bf16 inputs) and accumulated in fp32 on the matrix cores.
+ *    To keep every compute unit busy the token range of a tile may be split over several
+ *    workgroups, whose partial sums are then added to H with fp32 atomics: the summation order,
+ *    hence the last bits of H, can differ from run to run.
  * Errors: INVALID_ARG for NULL pointers, b <= 0, n_tok < 0, ldx < b, unknown xdt.
  *         n_tok == 0 is a no-op.
  */

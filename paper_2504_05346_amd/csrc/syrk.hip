@@ -25,6 +25,8 @@
 // Fallback kernel (k_syrk16; any alignment, any b): 8x8 patches are loaded with guarded scalar
 // loads, transposed in registers (v_perm_b32) and written to LDS already k-packed; fragment f
 // of a panel is the channel set {8x + f}, which keeps both LDS directions conflict-free.
+#include <algorithm>
+
 #include "common.h"
 #include "gemm_tile.h"
 
@@ -41,6 +43,7 @@ struct SyrkArgs {
   float alpha;
   int nt;      // tiles per side
   int ntiles;  // nt*(nt+1)/2
+  int nsplit;  // k-chunks per tile (main kernel only); > 1: partial sums are added atomically
 };
 
 // Logical tile index -> (ti, tj), ti >= tj.  Tiles are ordered by "super-rows" of 4 tile rows,
@@ -265,9 +268,15 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
   const int wm = wave / WN, wn = wave % WN;
   const int lo = lane & 31, hi = lane >> 5;
 
-  const int nwg = a.ntiles;
+  // Work item = (tile, k-chunk).  Hardware deals workgroups to the 8 XCDs round-robin; XCD x
+  // owns a contiguous range of the logical tile order and walks through it once per k-chunk,
+  // so that the 32 workgroups resident on an XCD share panels through its L2 and all XCDs are
+  // on the same chunk of tokens at the same time.
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int logical = xcd * (nwg >> 3) + min(xcd, nwg & 7) + local;
+  const int cnt = (a.ntiles >> 3) + (xcd < (a.ntiles & 7) ? 1 : 0);
+  if (local >= cnt * a.nsplit) return;  // uniform per workgroup, before any barrier
+  const int chunk = local / cnt;
+  const int logical = xcd * (a.ntiles >> 3) + min(xcd, a.ntiles & 7) + local % cnt;
   int ti, tj;
   tile_from_index(logical, a.nt, ti, tj);
   const int64_t i0 = (int64_t)ti * kSyTile, j0 = (int64_t)tj * kSyTile;
@@ -290,7 +299,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[f][g][r] = 0.f;
 
-  const int64_t nkt = (a.n_tok + kDmaKT - 1) / kDmaKT;
+  const int64_t nkt_all = (a.n_tok + kDmaKT - 1) / kDmaKT;
+  const int64_t kbeg = nkt_all * chunk / a.nsplit, nkt = nkt_all * (chunk + 1) / a.nsplit;
 
   // Descriptor and LDS destination of this wavefront's row loads of k-step kt (scalar
   // registers).  Steps past the end get an empty descriptor: every lane is out of range, nothing
@@ -344,19 +354,19 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
   constexpr int SLOTS = NMF / 2;                   // MFMAs that carry fragment reads
   constexpr int PER = (NFR + SLOTS - 1) / SLOTS;   // fragment reads behind each of them
   static_assert(RPW <= NMF - SLOTS, "one row load behind each MFMA of the second half");
-  issue(0);
-  issue(1);
-  issue(2);
-  issue(3);
+  issue(kbeg);
+  issue(kbeg + 1);
+  issue(kbeg + 2);
+  issue(kbeg + 3);
   __builtin_amdgcn_s_waitcnt(kWaitPrologue);
   __syncthreads();
   u32x4 a0[4], b0[GN], a1[4], b1[GN];
   {
-    const char* st = lds + lane_off;
+    const char* st = lds + (int)(kbeg % kDmaStages) * kDmaStageBytes + lane_off;
 #pragma unroll
     for (int k = 0; k < NFR; ++k) read_item(k, st, a0, b0);
   }
-  for (int64_t kt = 0; kt < nkt; ++kt) {
+  for (int64_t kt = kbeg; kt < nkt; ++kt) {
     {
       const char* st = lds + (int)(kt % kDmaStages) * kDmaStageBytes + lane_off + 16 * kDmaRow;
       __builtin_amdgcn_sched_barrier(0);
@@ -393,6 +403,25 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
 
   // H[i][j] += alpha * acc for i >= j; MFMA row m <-> channel i0 + 32(4wm+f) + m,
   // MFMA column n <-> channel j0 + 32(GN wn+g) + n: 32 lanes write 128 contiguous bytes.
+  if (a.nsplit > 1) {
+    // several workgroups hold partial sums of this tile: add them with device-scope atomics
+    // (no other access to H happens inside this launch)
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int g = 0; g < GN; ++g) {
+        const int64_t j = j0 + 32 * (GN * wn + g) + lo;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = 8 * (r >> 2) + 4 * hi + (r & 3);
+          const int64_t i = i0 + 32 * (4 * wm + f) + m;
+          if (i < a.b && j <= i)
+            (void)__hip_atomic_fetch_add(a.H + i * a.b + j, a.alpha * acc[f][g][r],
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    return;
+  }
   // per 32x32 MFMA tile: 16 loads, then 16 stores (a load behind a store would wait for it)
 #pragma unroll
   for (int f = 0; f < 4; ++f)
@@ -415,6 +444,30 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_syrk16_dma(SyrkArgs a) {
     }
 }
 
+// Number of k-chunks per tile.  One XCD (32 compute units) works through cnt*S items of
+// nkt/S k-steps each, plus a fixed cost per item (pipeline fill, write-out) of about `epi`
+// k-steps.  S = 1 keeps the plain read-modify-write (bitwise reproducible); it is given up only
+// for a gain of more than 3 %.
+static int choose_split(int ntiles, int64_t nkt) {
+  const int cnt = (ntiles + 7) / 8;
+  const double epi = 12.0;
+  auto cost = [&](int S) {
+    const int64_t rounds = ((int64_t)cnt * S + 31) / 32;
+    return (double)rounds * ((double)nkt / S + epi);
+  };
+  int best = 1;
+  double cbest = cost(1);
+  const int smax = (int)std::min<int64_t>(64, nkt / 64);
+  for (int S = 2; S <= smax; ++S) {
+    const double c = cost(S);
+    if (c < cbest * (best == 1 ? 0.97 : 1.0)) {
+      cbest = c;
+      best = S;
+    }
+  }
+  return best;
+}
+
 thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc,
                               thanos_dtype xdt, int64_t n_tok, int64_t ldx, float alpha) {
   if (n_tok == 0) return THANOS_OK;
@@ -432,6 +485,7 @@ thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc
   a.alpha = alpha;
   a.nt = (int)ceil_div(b, kSyTile);
   a.ntiles = a.nt * (a.nt + 1) / 2;
+  a.nsplit = 1;
   const bool vec = (reinterpret_cast<uintptr_t>(Xc) % 16 == 0) && (ldx % 8 == 0) && (b % 8 == 0);
   const size_t smem = vec ? (size_t)kDmaStages * kDmaStageBytes            // 136 KB
                           : 2 * kSyOct * 512 * sizeof(u32x4);              // 128 KB
@@ -441,7 +495,12 @@ thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc
   else kern = vec ? k_syrk16_dma<false, kNW> : k_syrk16<false, false>;
   THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-  hipLaunchKernelGGL(kern, dim3((unsigned)a.ntiles), dim3(vec ? 64 * kNW : 256), smem, s, a);
+  unsigned grid = (unsigned)a.ntiles;
+  if (vec) {
+    a.nsplit = choose_split(a.ntiles, (n_tok + kDmaKT - 1) / kDmaKT);
+    grid = 8u * (unsigned)((a.ntiles + 7) / 8) * (unsigned)a.nsplit;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(vec ? 64 * kNW : 256), smem, s, a);
   THANOS_LAUNCH_CHECK();
   return THANOS_OK;
 }
