@@ -17,7 +17,7 @@
 // Everything is fp32.
 #include <algorithm>
 
-#include "gemm_tile.h"
+#include "gemm_tile_x3.h"
 
 namespace thanos {
 
@@ -406,8 +406,8 @@ struct TrinvArgs {
   int nb, S;
 };
 
-__global__ __launch_bounds__(256) void k_trinv_T(TrinvArgs a) {
-  __shared__ GemmSmem sm;
+__global__ __launch_bounds__(kXThreads) void k_trinv_T(TrinvArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char sm[];
   const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
   const int base = 2 * p * a.S;
   const int gi = base + a.S + ti, gj = base + tj;
@@ -416,7 +416,8 @@ __global__ __launch_bounds__(256) void k_trinv_T(TrinvArgs a) {
   const float* B = a.Linv + ((int64_t)base * NB) * a.bp + (int64_t)gj * NB;  // [k][n]
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, tj * NB, a.S * NB, true, true);
+  gemm_tile_x3<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, tj * NB, a.S * NB, true, true);
+  if (threadIdx.x >= 256) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
   float* C = a.T + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB;
 #pragma unroll
@@ -428,8 +429,8 @@ __global__ __launch_bounds__(256) void k_trinv_T(TrinvArgs a) {
         C[(int64_t)acc_row(wm, f, r, lane) * a.bp + acc_col(wn, g, lane)] = acc.v[f][g][r];
 }
 
-__global__ __launch_bounds__(256) void k_trinv_X(TrinvArgs a) {
-  __shared__ GemmSmem sm;
+__global__ __launch_bounds__(kXThreads) void k_trinv_X(TrinvArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char sm[];
   const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
   const int base = 2 * p * a.S;
   const int gi = base + a.S + ti, gj = base + tj;
@@ -438,7 +439,8 @@ __global__ __launch_bounds__(256) void k_trinv_X(TrinvArgs a) {
   const float* B = a.T + ((int64_t)(base + a.S) * NB) * a.bp + (int64_t)gj * NB;     // [k][n]
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, 0, (ti + 1) * NB, true, true);
+  gemm_tile_x3<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, 0, (ti + 1) * NB, true, true);
+  if (threadIdx.x >= 256) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
   float* C = a.Linv + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB;
 #pragma unroll
@@ -552,12 +554,18 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   }
   if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
 
+  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_T),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kXSmemBytes));
+  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_X),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kXSmemBytes));
   for (int S = 1; S < nb; S *= 2) {
     TrinvArgs a{Ap, Linv, Tb, bp, nb, S};
     dim3 grid((unsigned)S, (unsigned)S, (unsigned)ceil_div(nb, 2 * S));
-    hipLaunchKernelGGL(k_trinv_T, grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_trinv_T, grid, dim3(kXThreads), kXSmemBytes, s, a);
     THANOS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_trinv_X, grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_trinv_X, grid, dim3(kXThreads), kXSmemBytes, s, a);
     THANOS_LAUNCH_CHECK();
   }
 

@@ -1,5 +1,6 @@
-// Plain fp32 matrix product on the matrix cores, used by the factorisation and the sweep.
-#include "gemm_tile.h"
+// fp32 matrix product (split-bf16 arithmetic on the matrix cores, see gemm_tile_x3.h), used by
+// the factorisation, the sweep and the fp32 Hessian accumulation.
+#include "gemm_tile_x3.h"
 
 namespace thanos {
 
@@ -15,8 +16,8 @@ struct GemmArgs {
 };
 
 template <bool AK, bool BK>
-__global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs g) {
-  __shared__ GemmSmem sm;
+__global__ __launch_bounds__(kXThreads) void k_gemm_f32(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char sm[];
   const int tn = blockIdx.x, tm = blockIdx.y;
   if (g.lower_only && tn > tm) return;
   const int m0 = tm * kTM, n0 = tn * kTN;
@@ -25,7 +26,8 @@ __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs g) {
   const float* B = BK ? g.B + n0 : g.B + (int64_t)n0 * g.ldb;
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, 0, g.K, g.vec_a, g.vec_b);
+  gemm_tile_x3<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, 0, g.K, g.vec_a, g.vec_b);
+  if (threadIdx.x >= 256) return;  // producer wavefronts hold no result
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   // Per 32x32 MFMA tile: 16 loads, then 16 stores.  A load placed right behind a store to the
@@ -64,14 +66,15 @@ thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, i
   GemmArgs g{A, B, C, lda, ldb, ldc, (int)M, (int)N, (int)K, alpha, beta, lower_only ? 1 : 0,
              vec_ok(A, lda) ? 1 : 0, vec_ok(B, ldb) ? 1 : 0};
   dim3 grid((unsigned)ceil_div(N, kTN), (unsigned)ceil_div(M, kTM));
-  if (!a_kmajor && !b_kmajor)
-    hipLaunchKernelGGL((k_gemm_f32<false, false>), grid, dim3(256), 0, s, g);
-  else if (!a_kmajor && b_kmajor)
-    hipLaunchKernelGGL((k_gemm_f32<false, true>), grid, dim3(256), 0, s, g);
-  else if (a_kmajor && b_kmajor)
-    hipLaunchKernelGGL((k_gemm_f32<true, true>), grid, dim3(256), 0, s, g);
-  else
-    hipLaunchKernelGGL((k_gemm_f32<true, false>), grid, dim3(256), 0, s, g);
+  void (*kern)(GemmArgs);
+  if (!a_kmajor && !b_kmajor) kern = k_gemm_f32<false, false>;
+  else if (!a_kmajor && b_kmajor) kern = k_gemm_f32<false, true>;
+  else if (a_kmajor && b_kmajor) kern = k_gemm_f32<true, true>;
+  else kern = k_gemm_f32<true, false>;
+  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kXSmemBytes));
+  hipLaunchKernelGGL(kern, grid, dim3(kXThreads), kXSmemBytes, s, g);
   THANOS_LAUNCH_CHECK();
   return THANOS_OK;
 }

@@ -1,0 +1,287 @@
+// 128x128 fp32 tile product on the CDNA4 bf16 matrix cores with three-way operand splitting.
+//
+// An fp32 value x is written as x = x1 + x2 + x3 with x1 = bf16(x), x2 = bf16(x - x1),
+// x3 = bf16(x - x1 - x2): 3 x 8 significant bits, the remainders are exact in fp32.  The product
+// a*b is then the sum of the six partial products whose weight is at least 2^-16 relative,
+//     a1 b1 + (a1 b2 + a2 b1) + (a1 b3 + a2 b2 + a3 b1),
+// each exact in the fp32 accumulator of v_mfma_f32_32x32x16_bf16; what is dropped is of order
+// 2^-24 |a||b|, the size of one fp32 rounding.  Six bf16 MFMAs of 32 cycles replace eight fp32
+// MFMAs (32x32x2) of 64 cycles for the same 32x32x16 block of products, and draw less power.
+//
+// One workgroup of 512 threads = 8 wavefronts, two per SIMD, with different jobs (a wavefront
+// cannot overlap its own vector arithmetic with its own MFMAs, two wavefronts of a SIMD can):
+//   wavefronts 0..3 (consumers): 2x2 arrangement, each owns 64x64 = 2x2 MFMA tiles of the
+//       accumulator (same layout as gemm_tile.h); per slab of 32 k-values they read their
+//       operands from LDS (16 bytes per lane and fragment) and issue 48 MFMAs;
+//   wavefronts 4..7 (producers): 4,5 fetch the A slab, 6,7 the B slab (32 floats per thread),
+//       split them in registers and store three bf16 planes per operand in LDS as
+//       [row][32 k] (row stride 80 bytes: the 16-byte reads of consecutive rows then cover all
+//       banks).  Global loads run two slabs ahead of the multiplication.
+// Two LDS buffers, one barrier per slab.  After the call only wavefronts 0..3 hold the result.
+#pragma once
+#include "gemm_tile.h"
+
+namespace thanos {
+
+constexpr int kXK = 32;                      // k-values per slab
+constexpr int kXRow = 80;                    // bytes per LDS row: 32 bf16 + 16 bytes of padding
+constexpr int kXPlane = 128 * kXRow;         // one bf16 plane of one operand
+constexpr int kXThreads = 512;
+constexpr size_t kXSmemBytes = 2 * 6 * (size_t)kXPlane;  // 122 880
+
+// LDS view: buf[2] x {a, b} x plane[3]
+__device__ __forceinline__ char* x3_plane(char* smem, int buf, int operand, int plane) {
+  return smem + ((buf * 2 + operand) * 3 + plane) * kXPlane;
+}
+
+// 32 floats of one operand slab held by a producer thread.
+//   !KMAJOR: v[q] = row m = (u >> 3) + 16 q, k = 4*(u & 7) .. +3.
+//    KMAJOR: v[q] = the four rows m = 4*(u & 31) .. +3 at k = 8*(u >> 5) + q.
+struct SlabRegsX3 {
+  float4 v[8];
+  uint32_t ok;  // fast path: bit q set = piece q is inside the operand (else v[q] is junk)
+};
+
+// Per-thread source of an operand: pointers to its eight 16-byte pieces of the slab at
+// k = kbeg, the step from one slab to the next, and how much of each piece exists.
+struct SlabSrcX3 {
+  const float* p[8];
+  int64_t step;  // floats between consecutive slabs
+  int kofs[8];   // k offset of piece q inside the slab
+  int nrow;      // KMAJOR: number of valid rows (0..4) of every piece
+  bool row_ok[8];
+};
+
+template <bool KMAJOR>
+__device__ __forceinline__ void slab_src_x3(SlabSrcX3& s, const float* __restrict__ P, int64_t ld,
+                                            int ext, int kbeg, int u) {
+  s.nrow = 4;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    if (KMAJOR) {
+      const int m4 = 4 * (u & 31);
+      s.kofs[q] = 8 * (u >> 5) + q;
+      s.p[q] = P + (int64_t)(kbeg + s.kofs[q]) * ld + m4;
+      s.nrow = min(4, max(0, ext - m4));
+      s.row_ok[q] = m4 < ext;
+    } else {
+      const int m = (u >> 3) + 16 * q;
+      s.kofs[q] = 4 * (u & 7);
+      s.p[q] = P + (int64_t)m * ld + kbeg + s.kofs[q];
+      s.row_ok[q] = m < ext;
+    }
+  }
+  s.step = KMAJOR ? (int64_t)kXK * ld : (int64_t)kXK;
+}
+
+// Loads slab number `it` (k0 = kbeg + it*kXK); krem = kend - k0 (<= 0: nothing is read).
+// FAST: every piece is either completely inside the operand or completely outside (the caller
+// checked alignment and that the extents are multiples of 4).  The loads are then issued
+// unconditionally (from a safe address when outside) and outside pieces are zeroed when the
+// slab is split: straight-line code with no early use of the data, so that the compiler can
+// keep the newer of the two slabs in flight while it waits for the older one.  Conditional
+// loads, or a select right behind the load, force it to wait for all of them.
+template <bool KMAJOR, bool FAST>
+__device__ __forceinline__ void slab_load_x3(SlabRegsX3& r, const SlabSrcX3& s, int it, int krem,
+                                             const float* __restrict__ safe) {
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const float* p = s.p[q] + (int64_t)it * s.step;
+    if (FAST) {
+      // no use of the loaded value here: the zeroing of outside pieces happens when the slab
+      // is split, so that nothing waits for these loads before then
+      const bool ok = s.row_ok[q] && s.kofs[q] < krem;
+      r.v[q] = *reinterpret_cast<const float4*>(ok ? p : safe);
+      if (q == 0) r.ok = 0;
+      r.ok |= ok ? (1u << q) : 0u;
+      continue;
+    }
+    float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (KMAJOR) {
+      if (s.kofs[q] < krem && s.row_ok[q]) {
+        val.x = p[0];
+        if (s.nrow > 1) val.y = p[1];
+        if (s.nrow > 2) val.z = p[2];
+        if (s.nrow > 3) val.w = p[3];
+      }
+    } else {
+      const int kr = krem - s.kofs[q];  // valid k-values from this piece on
+      if (s.row_ok[q] && kr > 0) {
+        val.x = p[0];
+        if (kr > 1) val.y = p[1];
+        if (kr > 2) val.z = p[2];
+        if (kr > 3) val.w = p[3];
+      }
+    }
+    r.v[q] = val;
+  }
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Split two floats into three packed bf16 pairs (conversion = the packed two-at-a-time
+// instruction, the way back is a shift / a mask).
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t (&packed)[3]) {
+  f32x2 v = {x0, x1};
+#pragma unroll
+  for (int p = 0; p < 3; ++p) {
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    packed[p] = __builtin_bit_cast(uint32_t, h);
+    if (p < 2) {
+      v[0] -= __uint_as_float(packed[p] << 16);
+      v[1] -= __uint_as_float(packed[p] & 0xffff0000u);
+    }
+  }
+}
+
+template <bool KMAJOR, bool MASKED>
+__device__ __forceinline__ void slab_store_x3(char* smem, int buf, int operand,
+                                              const SlabRegsX3& rin, int u) {
+  SlabRegsX3 r = rin;
+  if (MASKED) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (!((r.ok >> q) & 1)) r.v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  char* pl[3] = {x3_plane(smem, buf, operand, 0), x3_plane(smem, buf, operand, 1),
+                 x3_plane(smem, buf, operand, 2)};
+  if (KMAJOR) {
+    // row m4 + mm: the 8 k-values 8*(u>>5) .. +7 -> 16 bytes per plane
+    const int m4 = 4 * (u & 31), kb = 16 * (u >> 5);
+#pragma unroll
+    for (int mm = 0; mm < 4; ++mm) {
+      float c[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        c[q] = mm == 0 ? r.v[q].x : mm == 1 ? r.v[q].y : mm == 2 ? r.v[q].z : r.v[q].w;
+      u32x4 o[3];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        uint32_t pk[3];
+        split2(c[2 * e], c[2 * e + 1], pk);
+        o[0][e] = pk[0];
+        o[1][e] = pk[1];
+        o[2][e] = pk[2];
+      }
+#pragma unroll
+      for (int p = 0; p < 3; ++p)
+        *reinterpret_cast<u32x4*>(pl[p] + (m4 + mm) * kXRow + kb) = o[p];
+    }
+  } else {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      uint32_t lo2[3], hi2[3];
+      split2(r.v[q].x, r.v[q].y, lo2);
+      split2(r.v[q].z, r.v[q].w, hi2);
+      const int off = ((u >> 3) + 16 * q) * kXRow + 8 * (u & 7);
+#pragma unroll
+      for (int p = 0; p < 3; ++p)
+        *reinterpret_cast<uint2*>(pl[p] + off) = make_uint2(lo2[p], hi2[p]);
+    }
+  }
+}
+
+// Producer loop of one operand: load slabs two ahead, split and store them into the two LDS
+// buffers in turn, one barrier per slab (the consumers run the same barrier sequence).
+template <bool KMAJOR, bool FAST, bool MASKED>
+__device__ __forceinline__ void x3_produce(char* smem, int operand, const float* __restrict__ P,
+                                           int64_t ld, int ext, int kbeg, int kend, int nslab,
+                                           int u) {
+  SlabSrcX3 src;
+  slab_src_x3<KMAJOR>(src, P, ld, ext, kbeg, u);
+  SlabRegsX3 r0, r1;
+  slab_load_x3<KMAJOR, FAST>(r0, src, 0, kend - kbeg, P);
+  slab_load_x3<KMAJOR, FAST>(r1, src, 1, kend - kbeg - kXK, P);
+  slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r0, u);
+  __syncthreads();  // slab 0 is in buffer 0
+  for (int it = 0; it < nslab; it += 2) {
+    // consumers multiply slab `it` from buffer 0
+    slab_load_x3<KMAJOR, FAST>(r0, src, it + 2, kend - kbeg - (it + 2) * kXK, P);
+    if (it + 1 < nslab) slab_store_x3<KMAJOR, MASKED>(smem, 1, operand, r1, u);
+    __syncthreads();
+    if (it + 1 >= nslab) break;
+    // consumers multiply slab `it + 1` from buffer 1
+    slab_load_x3<KMAJOR, FAST>(r1, src, it + 3, kend - kbeg - (it + 3) * kXK, P);
+    if (it + 2 < nslab) slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r0, u);
+    __syncthreads();
+  }
+}
+
+// acc += op(A)[0:128, kbeg:kend] * op(B)[kbeg:kend, 0:128]; arguments as in gemm_tile(), smem =
+// kXSmemBytes of LDS, called by all 512 threads; the result is in wavefronts 0..3.
+template <bool A_KMAJOR, bool B_KMAJOR>
+__device__ __forceinline__ void gemm_tile_x3(TileAcc& acc, char* smem, const float* __restrict__ A,
+                                             int64_t lda, int m_ext, const float* __restrict__ B,
+                                             int64_t ldb, int n_ext, int kbeg, int kend, bool vec_a,
+                                             bool vec_b) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (kend <= kbeg) return;
+  const int nslab = (kend - kbeg + kXK - 1) / kXK;
+  __syncthreads();  // previous users of the LDS buffers are done
+  if (wave >= 4) {
+    // ---------------------------------------------------------------- producers
+    // fast path: aligned operand whose extent along the 4-element pieces is a multiple of 4
+    const int u = tid & 127;
+    // fast: aligned operand whose extent along the 4-element pieces is a multiple of 4;
+    // whole: all 128 rows exist and the k range is a whole number of slabs (nothing to zero)
+    const bool ktail = (kend - kbeg) % kXK != 0;
+    if (wave >= 6) {
+      const bool fast = vec_b && (B_KMAJOR ? n_ext % 4 == 0 : (kend - kbeg) % 4 == 0);
+      const bool whole = n_ext == 128 && !ktail;
+      if (fast && whole) x3_produce<B_KMAJOR, true, false>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
+      else if (fast) x3_produce<B_KMAJOR, true, true>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
+      else x3_produce<B_KMAJOR, false, false>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
+    } else {
+      const bool fast = vec_a && (A_KMAJOR ? m_ext % 4 == 0 : (kend - kbeg) % 4 == 0);
+      const bool whole = m_ext == 128 && !ktail;
+      if (fast && whole) x3_produce<A_KMAJOR, true, false>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
+      else if (fast) x3_produce<A_KMAJOR, true, true>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
+      else x3_produce<A_KMAJOR, false, false>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
+    }
+  } else {
+    // ---------------------------------------------------------------- consumers
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lo = lane & 31, hi = lane >> 5;
+    const int a_off = (wm * 64 + lo) * kXRow + 16 * hi;
+    const int b_off = (wn * 64 + lo) * kXRow + 16 * hi;
+    auto compute = [&](int buf) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 af[2][3], bf[2][3];
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+          for (int p = 0; p < 3; ++p) {
+            af[f][p] = *reinterpret_cast<const bf16x8*>(x3_plane(smem, buf, 0, p) + a_off +
+                                                        f * 32 * kXRow + 32 * ks);
+            bf[f][p] = *reinterpret_cast<const bf16x8*>(x3_plane(smem, buf, 1, p) + b_off +
+                                                        f * 32 * kXRow + 32 * ks);
+          }
+        // smallest partial products first; consecutive MFMAs go to different accumulators
+        constexpr int pa[6] = {2, 1, 0, 1, 0, 0};
+        constexpr int pb[6] = {0, 1, 2, 0, 1, 0};
+#pragma unroll
+        for (int t = 0; t < 6; ++t)
+#pragma unroll
+          for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+              acc.v[f][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[f][pa[t]], bf[g][pb[t]],
+                                                                    acc.v[f][g], 0, 0, 0);
+      }
+    };
+    __syncthreads();  // slab 0 is in buffer 0
+    for (int it = 0; it < nslab; it += 2) {
+      compute(0);
+      __syncthreads();
+      if (it + 1 >= nslab) break;
+      compute(1);
+      __syncthreads();
+    }
+  }
+}
+
+}  // namespace thanos

@@ -10,7 +10,7 @@
 // All P_k are produced by one batched launch before the sweep.
 #include <algorithm>
 
-#include "gemm_tile.h"
+#include "gemm_tile_x3.h"
 
 namespace thanos {
 
@@ -85,8 +85,8 @@ struct BlockRowsArgs {
   int vec;
 };
 
-__global__ __launch_bounds__(256) void k_block_rows(BlockRowsArgs a) {
-  __shared__ GemmSmem sm;
+__global__ __launch_bounds__(kXThreads) void k_block_rows(BlockRowsArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char sm[];
   const int64_t j1 = (int64_t)blockIdx.y * a.B;
   const int bw = (int)min((int64_t)a.B, a.b - j1);
   const int64_t col0 = j1 + (int64_t)blockIdx.x * kTN;
@@ -98,7 +98,8 @@ __global__ __launch_bounds__(256) void k_block_rows(BlockRowsArgs a) {
   const float* Bm = a.U + j1 * a.b + col0;       // (k,n) at B[k*b + n]
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<true, true>(acc, sm, A, a.b, m_ext, Bm, a.b, n_ext, 0, bw, a.vec, a.vec);
+  gemm_tile_x3<true, true>(acc, sm, A, a.b, m_ext, Bm, a.b, n_ext, 0, bw, a.vec, a.vec);
+  if (threadIdx.x >= 256) return;  // producer wavefronts hold no result
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
   for (int f = 0; f < 2; ++f)
@@ -769,8 +770,8 @@ struct UpdateArgs {
   int K, ldl, vec_a, vec_b;
 };
 
-__global__ __launch_bounds__(256) void k_update(UpdateArgs a) {
-  __shared__ GemmSmem sm;
+__global__ __launch_bounds__(kXThreads) void k_update(UpdateArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char sm[];
   const int64_t m0 = (int64_t)blockIdx.y * kTM;
   const int64_t n0 = a.col0 + (int64_t)blockIdx.x * kTN;
   const int m_ext = (int)min((int64_t)kTM, a.c - m0);
@@ -779,7 +780,8 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a) {
   const float* Bm = a.P + a.prow0 * a.b + n0;   // (k,n) at B[k*b + n]
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
+  gemm_tile_x3<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
+  if (threadIdx.x >= 256) return;  // producer wavefronts hold no result
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
   const int64_t j2 = a.zj2;
   const bool in_block = n0 < j2 && n0 + kTN > a.zj1;  // tile overlaps the columns holding masks
@@ -907,7 +909,13 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     BlockRowsArgs a{U, w.P, b, B,
                     (aligned_b && reinterpret_cast<uintptr_t>(U) % 16 == 0) ? 1 : 0};
     dim3 grid((unsigned)ceil_div(b, kTN), (unsigned)ceil_div(b, B), (unsigned)ceil_div(B, kTM));
-    hipLaunchKernelGGL(k_block_rows, grid, dim3(256), 0, s, a);
+    THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_block_rows),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kXSmemBytes));
+    THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_update),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kXSmemBytes));
+    hipLaunchKernelGGL(k_block_rows, grid, dim3(kXThreads), kXSmemBytes, s, a);
     THANOS_LAUNCH_CHECK();
   }
 
@@ -987,7 +995,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
                     (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
       dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
-      hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
+      hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, s, ua);
       THANOS_LAUNCH_CHECK();
     }
     if (super > 1 && j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block
@@ -999,7 +1007,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
                       (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
         dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
-        hipLaunchKernelGGL(k_update, grid, dim3(256), 0, aux.stream, ua);
+        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, aux.stream, ua);
         THANOS_LAUNCH_CHECK();
       }
       if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
@@ -1007,7 +1015,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
                       (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
         dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
-        hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, ua);
+        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, s, ua);
         THANOS_LAUNCH_CHECK();
       }
       if (next_end < b) {
