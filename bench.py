@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--sparsity", type=float, default=0.5)
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--damping", type=float, default=0.01)
+    ap.add_argument("--outlier-fraction", type=float, default=0.0,
+                    help="alpha of the n:m algorithm: share of rows (largest loss) left dense")
     ap.add_argument("--chunks", type=int, default=1,
                     help="number of thanos_hessian_accumulate calls the tokens are split into")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -98,7 +100,8 @@ def cpu_baseline(args, W, X, torch):
     t_f = time.perf_counter() - t0
     t0 = time.perf_counter()
     orc.prune_fast(Ws, Hs, mode=args.mode, p=args.sparsity, n=args.n, m=args.m, B=args.block,
-                   damp=args.damping, U=U)
+                   damp=args.damping, U=U,
+                   alpha=args.outlier_fraction if args.mode == "nm" else 0)
     t_s = time.perf_counter() - t0
     est = t_h * (args.tokens / tok_s) + t_f + t_s * (args.c / rows_s)
     return {
@@ -133,7 +136,7 @@ def main():
     c, b, T = args.c, args.b, args.tokens
     o = th.PruneOpts(mode=th.THANOS_NM if args.mode == "nm" else th.THANOS_UNSTRUCTURED,
                      sparsity=args.sparsity, n=args.n, m=args.m, block_size=args.block,
-                     damping=args.damping)
+                     damping=args.damping, outlier_fraction=args.outlier_fraction)
     nbytes = th.thanos_prune_workspace_bytes(c, b, o)
     assert nbytes > 0
     ws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
@@ -179,7 +182,8 @@ def main():
     kept = int((M == 0).sum().item())
     workload = (f"{c}x{b} fp16 layer, {T} fp16 calibration tokens, "
                 + (f"{args.n}:{args.m}" if args.mode == "nm" else f"{args.sparsity:g} unstructured")
-                + f", block {args.block}, damping {args.damping:g}")
+                + f", block {args.block}, damping {args.damping:g}"
+                + (f", outlier rows {args.outlier_fraction:g}" if args.outlier_fraction else ""))
     out = {
         "metric": "ms per linear layer pruned (4096x11008, 2:4); MFMA% / HBM GB/s per phase",
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps,

@@ -61,6 +61,11 @@ typedef struct {
   const float* factor_in;  /* optional U (b*b) from thanos_factor for this H and damping;
                               NULL = factor inside the call                                   */
   const float* xnorm2_in;  /* required with factor_in: xnorm2 (b) from the same call          */
+  double outlier_fraction; /* alpha in [0,1) of the n:m algorithm (App. G.4.4, Sec. 4.7 "Outlier
+                              rows"): the ceil(alpha*c) rows with the largest loss
+                              h_i = ||W_i X||^2 = W_i H W_i^T are left untouched (dense, mask 0);
+                              ties by row index.  0 = prune every row.  THANOS_NM only; needs H
+                              (undamped) even when factor_in is given.                          */
 } thanos_prune_opts;
 
 /*
@@ -118,8 +123,9 @@ size_t thanos_factor_workspace_bytes(int64_t b);
  * it is set to -(i+1) if the system of row i met a non-positive pivot (that row's update is
  * then meaningless; other rows are unaffected).
  * Ties in the metric are broken by ascending (row, column).
- * Errors: INVALID_ARG (NULL, sizes, n/m/B constraints, p outside [0,1)), UNSUPPORTED
- * (block_size > 256, m > 16), WORKSPACE, HIP.
+ * Errors: INVALID_ARG (NULL, sizes, n/m/B constraints, p or alpha outside [0,1), alpha > 0
+ * without H), UNSUPPORTED (block_size > 256, m > 16, alpha > 0 with THANOS_UNSTRUCTURED),
+ * WORKSPACE, HIP.
  */
 thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                                  const float* H, const thanos_prune_opts* opts /* host */,

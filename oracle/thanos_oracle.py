@@ -22,7 +22,9 @@ What is followed
                             Delta = -u R_hat^{-1} R.
   * Unstructured sweep:     Alg. 1 (global residual mask, local block mask,
                             r <- r - ||M||_F^2, residual Hessian re-inverted per block).
-  * n:m sweep:              the n:m algorithm of App. G.4.4 with alpha = 0.
+  * n:m sweep:              the n:m algorithm of App. G.4.4; alpha > 0 (outlier rows,
+                            Sec. 4.7 "Outlier rows"): row losses h_i = ||W_i X||^2, the
+                            ceil(alpha*c) rows with the largest loss are not pruned.
   * Magnitude pruning:      Sec. 3.1 / App. F.1 (comparator for the sanity bound).
 
 Readings taken where the paper is silent or inconsistent (each is listed in the
@@ -38,6 +40,10 @@ design notes of the repository as well):
     decision), computed as fl32(|fl32(W)|) * fl32(sqrt(fl32(diag H))).
   * n:m: per row and per group of m consecutive columns, the n smallest-metric
     weights are removed (n = number of zeros per group).
+  * outlier rows: their number is ceil(alpha*c) (the text), hence c - ceil(alpha*c) rows
+    are pruned (the listing's loop bound ceil(c(1-alpha)) differs when alpha*c is not an
+    integer); rows are ranked by ascending (h_i, i) and the last ones are the outliers;
+    alpha is evaluated exactly on its decimal value; the row loss uses the undamped H.
   * removed weights are set to exactly 0.
 
 parity status: every function below is pinned by tests/test_oracle_*.py
@@ -48,6 +54,7 @@ those step-level ones and the literal == single-factorisation identity.
 """
 from __future__ import annotations
 
+import math
 from fractions import Fraction
 from typing import Optional, Tuple
 
@@ -199,10 +206,41 @@ def prune_unstructured(W: np.ndarray, H: np.ndarray, p, B: int, damp: float,
     return W, M_full
 
 
+def row_losses(W: np.ndarray, H: np.ndarray) -> np.ndarray:
+    """h_i = ||W_i X||_2^2 = W_i H W_i^T (Sec. 4.7, eq. (row outlier loss)), H = X^T X."""
+    W = np.asarray(W, dtype=np.float64)
+    return np.einsum("ij,ij->i", W @ np.asarray(H, dtype=np.float64), W)
+
+
+def num_outlier_rows(alpha, c: int) -> int:
+    """ceil(alpha*c), evaluated exactly on the decimal value of alpha."""
+    a = Fraction(str(alpha)) if not isinstance(alpha, Fraction) else alpha
+    if not (0 <= a < 1):
+        raise ValueError("alpha must be in [0, 1)")
+    return int(math.ceil(a * c))
+
+
+def pruned_rows(W: np.ndarray, H: np.ndarray, alpha, dtype=np.float64) -> np.ndarray:
+    """Boolean vector: True for the rows that are pruned, False for the ceil(alpha*c) outlier
+    rows (largest row loss; ascending (h, row) order, the rows permutation of App. G.4.3
+    without moving anything).  `dtype` is the precision in which the ranking is taken."""
+    c = W.shape[0]
+    n_out = num_outlier_rows(alpha, c)
+    h = row_losses(W, H).astype(dtype)
+    order = np.lexsort((np.arange(c), h))        # ascending h, ties by row index
+    keep = np.ones(c, dtype=bool)
+    if n_out:
+        keep[order[c - n_out:]] = False
+    return keep
+
+
 def prune_nm(W: np.ndarray, H: np.ndarray, n: int, m: int, B: int, damp: float,
              metric_dtype=np.float32,
-             return_margins: bool = False):
-    """n:m algorithm of App. G.4.4 with alpha = 0.  Returns (W_hat, M[, margins]).
+             return_margins: bool = False, alpha=0, rows: Optional[np.ndarray] = None):
+    """n:m algorithm of App. G.4.4.  Returns (W_hat, M[, margins]).
+
+    alpha > 0: the outlier rows (see pruned_rows) are skipped: no mask, no update.
+    `rows` (boolean, c) overrides the choice of pruned rows.
 
     margins has one entry per (row, group): relative gap between the n-th and
     the (n+1)-th smallest metric of the group at the time it was decided.
@@ -213,14 +251,18 @@ def prune_nm(W: np.ndarray, H: np.ndarray, n: int, m: int, B: int, damp: float,
         raise ValueError("m must divide both b and B")
     xn2 = np.diag(H).astype(np.float64)
     Hd = damped(H, damp)
+    if rows is None:
+        rows = pruned_rows(W, H, alpha)
     M_full = np.zeros((c, b), dtype=np.uint8)
     margins = np.zeros((c, b // m))
     for j1, j2 in _blocks(b, B):
         Hinv = np.linalg.inv(Hd[j1:, j1:])
         M = nm_mask(W[:, j1:j2], xn2[j1:j2], n, m, metric_dtype)
+        M[~rows] = 0
         if return_margins:
             margins[:, j1 // m:j2 // m] = _group_margins(W[:, j1:j2], xn2[j1:j2], n, m,
                                                          metric_dtype)
+            margins[~rows, j1 // m:j2 // m] = np.inf   # nothing is decided in outlier rows
         for i in range(c):
             q = phi(M[i])
             W[i, j1:] = row_update(W[i, j1:], Hinv, q)
@@ -263,7 +305,8 @@ def inverse_factor(Hd: np.ndarray) -> np.ndarray:
 def prune_fast(W: np.ndarray, H: np.ndarray, *, mode: str, p=None, n: int = 0, m: int = 0,
                B: int, damp: float, metric_dtype=np.float32,
                mask_in: Optional[np.ndarray] = None,
-               U: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+               U: Optional[np.ndarray] = None, alpha=0,
+               rows: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
     """Same sweeps as prune_unstructured / prune_nm, but every residual inverse is
     read off one factor U (see inverse_factor) and the row loop is vectorised per
     group of rows that share a count s.  mask_in (c x b) forces the mask.
@@ -273,6 +316,8 @@ def prune_fast(W: np.ndarray, H: np.ndarray, *, mode: str, p=None, n: int = 0, m
     xn2 = np.diag(H).astype(np.float64)
     if U is None:
         U = inverse_factor(damped(H, damp))
+    if rows is None:
+        rows = pruned_rows(W, H, alpha) if mode == "nm" else np.ones(c, dtype=bool)
     M_full = np.zeros((c, b), dtype=np.uint8)
     r = num_to_remove(p, c, b) if mode == "unstructured" else 0
     for j1, j2 in _blocks(b, B):
@@ -285,6 +330,7 @@ def prune_fast(W: np.ndarray, H: np.ndarray, *, mode: str, p=None, n: int = 0, m
             r -= int(M.sum())
         elif mode == "nm":
             M = nm_mask(W[:, j1:j2], xn2[j1:j2], n, m, metric_dtype)
+            M[~rows] = 0
         else:
             raise ValueError(mode)
         G = Rows[:, :j2 - j1]

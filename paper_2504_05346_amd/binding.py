@@ -36,6 +36,7 @@ class PruneOpts(ctypes.Structure):
         ("mask_in", ctypes.c_void_p),
         ("factor_in", ctypes.c_void_p),
         ("xnorm2_in", ctypes.c_void_p),
+        ("outlier_fraction", ctypes.c_double),
     ]
 
 

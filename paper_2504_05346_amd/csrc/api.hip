@@ -7,11 +7,11 @@ namespace thanos {
 size_t factor_workspace_bytes(int64_t b);
 thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
                      float* xnorm2, void* ws, int32_t* info);
-size_t sweep_workspace_bytes(int64_t c, int64_t b, int B);
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers);
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
-                    const float* U, const float* xnorm2, const thanos_prune_opts* o,
-                    long long r_total, float* W, void* W_cast, uint8_t* mask, void* ws,
-                    int32_t* info);
+                    const float* H, const float* U, const float* xnorm2,
+                    const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info);
 __global__ void k_zero_info(int32_t* info) { *info = 0; }
 }  // namespace thanos
 
@@ -28,6 +28,16 @@ static long long num_to_remove(double p, int64_t c, int64_t b) {
   return r;
 }
 
+// Number of outlier rows, ceil(alpha*c), with alpha read as the short decimal it prints as: a
+// product that lands within 1e-6 above an integer is that integer (0.1 * 1000 -> 100, not 101).
+static long long num_outlier_rows(double alpha, int64_t c) {
+  if (!(alpha > 0.0)) return 0;
+  const long double x = (long double)alpha * (long double)c;
+  long long n = (long long)ceill(x);
+  if (x - (long double)(n - 1) < 1e-6L) n -= 1;
+  return n < 0 ? 0 : (n > c ? c : n);
+}
+
 static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b) {
   if (!o) return THANOS_ERR_INVALID_ARG;
   if (o->mode != THANOS_UNSTRUCTURED && o->mode != THANOS_NM) return THANOS_ERR_INVALID_ARG;
@@ -41,6 +51,8 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
     if (o->m > 16) return THANOS_ERR_UNSUPPORTED;
   }
   if (o->factor_in && !o->xnorm2_in) return THANOS_ERR_INVALID_ARG;
+  if (!(o->outlier_fraction >= 0.0 && o->outlier_fraction < 1.0)) return THANOS_ERR_INVALID_ARG;
+  if (o->outlier_fraction > 0.0 && o->mode != THANOS_NM) return THANOS_ERR_UNSUPPORTED;
   if (o->block_size > 256) return THANOS_ERR_UNSUPPORTED;
   (void)c;
   return THANOS_OK;
@@ -86,7 +98,7 @@ thanos_status thanos_factor(const float* H, int64_t b, float damping, float* U, 
 
 size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opts* opts) {
   if (c <= 0 || b <= 0 || check_opts(opts, c, b) != THANOS_OK) return 0;
-  size_t n = sweep_workspace_bytes(c, b, opts->block_size);
+  size_t n = sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
   if (!opts->factor_in) {
     n += align_up((size_t)b * b * sizeof(float), 256);  // U
     n += align_up((size_t)b * sizeof(float), 256);      // xnorm2
@@ -104,6 +116,7 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
   thanos_status st = check_opts(opts, c, b);
   if (st != THANOS_OK) return st;
   if (!opts->factor_in && !H) return THANOS_ERR_INVALID_ARG;
+  if (opts->outlier_fraction > 0.0 && !H) return THANOS_ERR_INVALID_ARG;  // row losses need H
   if (b > 65535 || c > ((int64_t)1 << 24)) return THANOS_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < thanos_prune_workspace_bytes(c, b, opts)) return THANOS_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
@@ -111,7 +124,7 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
 
   char* p = reinterpret_cast<char*>(ws);
   void* sweep_ws = p;
-  p += sweep_workspace_bytes(c, b, opts->block_size);
+  p += sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
   const float* U = opts->factor_in;
   const float* xn2 = opts->xnorm2_in;
   if (!U) {
@@ -129,8 +142,9 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
   }
   const long long r_total =
       (opts->mode == THANOS_UNSTRUCTURED) ? num_to_remove(opts->sparsity, c, b) : 0;
-  return sweep(s, W_in, wdt, c, b, U, xn2, opts, r_total, W_out, W_out_cast, mask_out, sweep_ws,
-               info_dev);
+  const long long n_out = num_outlier_rows(opts->outlier_fraction, c);
+  return sweep(s, W_in, wdt, c, b, H, U, xn2, opts, r_total, n_out, W_out, W_out_cast, mask_out,
+               sweep_ws, info_dev);
 }
 
 }  // extern "C"

@@ -10,6 +10,8 @@
 // All P_k are produced by one batched launch before the sweep.
 #include <algorithm>
 
+#include <cmath>
+
 #include "gemm_tile_x3.h"
 
 namespace thanos {
@@ -338,6 +340,7 @@ struct SolveArgs {
   const SelState* st;    // SEL_THRESHOLD
   SelState* st_rw;
   const int* row_eq;     // exclusive tie prefix per row
+  const uint8_t* row_skip;  // optional, c bytes: 1 = row is left untouched (outlier row)
   int32_t* info;
   int64_t c, b, j1;
   int bw, ldl, n, m;
@@ -398,6 +401,10 @@ __global__ __launch_bounds__(64 * WPB, (RPL == 1 ? 2 : 1)) void k_solve(SolveArg
         }
         sel[r] = rank < a.n;
       }
+    }
+    if (a.row_skip && a.row_skip[i]) {
+#pragma unroll
+      for (int r = 0; r < CPL; ++r) sel[r] = false;
     }
   } else {  // SEL_THRESHOLD: key < tau, or key == tau and among the first need_eq ties
     const bool none = a.st->none != 0;
@@ -624,6 +631,7 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
       }
       sel = rank < a.n;
     }
+    if (a.row_skip && a.row_skip[i]) sel = false;
   } else {  // SEL_THRESHOLD
     const bool none = a.st->none != 0;
     const unsigned int tau = a.st->tau;
@@ -814,6 +822,58 @@ __global__ __launch_bounds__(kXThreads) void k_update(UpdateArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Outlier rows (App. G.4.4 / Sec. 4.7): h_i = ||W_i X||^2 = W_i H W_i^T; the ceil(alpha c) rows
+// with the largest h are left untouched.
+// Hf = symmetric copy of the lower triangle of H (32x32 tiles through LDS).
+__global__ __launch_bounds__(256) void k_mirror_lower(const float* __restrict__ H, int64_t b,
+                                                      float* __restrict__ Hf) {
+  __shared__ float t[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int64_t i0 = (int64_t)blockIdx.y * 32, j0 = (int64_t)blockIdx.x * 32;
+  if (j0 > i0) return;  // tiles on and below the diagonal write themselves and their mirror
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t i = i0 + r, j = j0 + tx;
+    float v = 0.f;
+    if (i < b && j < b) v = (j <= i) ? H[i * b + j] : H[j * b + i];
+    t[r][tx] = v;
+    if (i < b && j < b) Hf[i * b + j] = v;
+  }
+  __syncthreads();
+  if (i0 == j0) return;
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t i = j0 + r, j = i0 + tx;  // mirrored tile
+    if (i < b && j < b) Hf[i * b + j] = t[tx][r];
+  }
+}
+
+// h[i] = sum_j T[i][j] * W[i][j]; one wavefront per row, fp64 sum in a fixed order.
+__global__ __launch_bounds__(256) void k_rowdot(const float* __restrict__ T,
+                                                const float* __restrict__ W, int64_t c, int64_t b,
+                                                float* __restrict__ h) {
+  const int lane = threadIdx.x & 63;
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= c) return;
+  double acc = 0.0;
+  for (int64_t j = lane; j < b; j += 64) acc += (double)T[i * b + j] * (double)W[i * b + j];
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+  if (lane == 0) h[i] = (float)acc;
+}
+
+// skip[i] = 1 for the n_out rows with the largest (h, row) (ascending order, ties by row index).
+__global__ __launch_bounds__(256) void k_row_rank(const float* __restrict__ h, int64_t c,
+                                                  int64_t n_out, uint8_t* __restrict__ skip) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= c) return;
+  const float mine = h[i];
+  int64_t rank = 0;
+  for (int64_t k = 0; k < c; ++k) {
+    const float o = h[k];
+    rank += (o < mine || (o == mine && k < i)) ? 1 : 0;
+  }
+  skip[i] = rank >= c - n_out ? 1 : 0;
+}
+
+// ------------------------------------------------------------------------------------------
 struct SweepWs {
   float* sx;
   float* Lam;
@@ -822,6 +882,10 @@ struct SweepWs {
   SelState* st;
   int* row_cand;
   int* row_eq;
+  float* Hf;        // alpha > 0: symmetric copy of H, b x b
+  float* T;         // alpha > 0: W * H, c x b
+  float* h;         // alpha > 0: row losses, c
+  uint8_t* row_skip;  // alpha > 0: c
 };
 
 static char* carve(char*& p, size_t bytes) {
@@ -836,7 +900,7 @@ static char* carve(char*& p, size_t bytes) {
 // kSuper times longer reduction (the multipliers of all its blocks are kept, c x kSuper*B).
 constexpr int kSuper = 8;
 
-size_t sweep_workspace_bytes(int64_t c, int64_t b, int B) {
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers) {
   size_t n = 0;
   n += align_up((size_t)b * 4, 256);            // sx
   n += align_up((size_t)c * B * kSuper * 4 * 2, 256);  // Lam, two super-block buffers
@@ -844,10 +908,16 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B) {
   n += align_up(2048 * 4, 256);                 // hist
   n += align_up(sizeof(SelState), 256);         // state
   n += 2 * align_up((size_t)c * 4, 256);        // row_cand, row_eq
+  if (outliers) {
+    n += align_up((size_t)b * b * 4, 256);      // Hf
+    n += align_up((size_t)c * b * 4, 256);      // T
+    n += align_up((size_t)c * 4, 256);          // h
+    n += align_up((size_t)c, 256);              // row_skip
+  }
   return n;
 }
 
-static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B) {
+static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers) {
   char* p = reinterpret_cast<char*>(ws);
   SweepWs w;
   w.sx = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
@@ -857,6 +927,14 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B) {
   w.st = reinterpret_cast<SelState*>(carve(p, sizeof(SelState)));
   w.row_cand = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
   w.row_eq = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
+  w.Hf = w.T = w.h = nullptr;
+  w.row_skip = nullptr;
+  if (outliers) {
+    w.Hf = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
+    w.T = reinterpret_cast<float*>(carve(p, (size_t)c * b * 4));
+    w.h = reinterpret_cast<float*>(carve(p, (size_t)c * 4));
+    w.row_skip = reinterpret_cast<uint8_t*>(carve(p, (size_t)c));
+  }
   return w;
 }
 
@@ -885,11 +963,12 @@ static void launch_solve(hipStream_t s, const SolveArgs& a, int smax) {
 }
 
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
-                    const float* U, const float* xnorm2, const thanos_prune_opts* o,
-                    long long r_total, float* W, void* W_cast, uint8_t* mask, void* ws,
-                    int32_t* info) {
+                    const float* H, const float* U, const float* xnorm2,
+                    const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info) {
   const int B = o->block_size;
-  SweepWs w = carve_ws(ws, c, b, B);
+  const bool outliers = n_out > 0;
+  SweepWs w = carve_ws(ws, c, b, B, outliers);
   const int64_t n = c * b;
   const unsigned nblk = (unsigned)ceil_div(n, 256);
 
@@ -903,6 +982,18 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   THANOS_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_sqrt, dim3((unsigned)ceil_div(b, 256)), dim3(256), 0, s, xnorm2, w.sx, b);
   THANOS_LAUNCH_CHECK();
+  if (outliers) {
+    hipLaunchKernelGGL(k_mirror_lower, dim3((unsigned)ceil_div(b, 32), (unsigned)ceil_div(b, 32)),
+                       dim3(256), 0, s, H, b, w.Hf);
+    THANOS_LAUNCH_CHECK();
+    thanos_status st = gemm_f32(s, false, true, c, b, b, 1.f, W, b, w.Hf, b, 0.f, w.T, b, false);
+    if (st != THANOS_OK) return st;
+    hipLaunchKernelGGL(k_rowdot, dim3((unsigned)ceil_div(c, 4)), dim3(256), 0, s, w.T, W, c, b, w.h);
+    THANOS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_row_rank, dim3((unsigned)ceil_div(c, 256)), dim3(256), 0, s, w.h, c,
+                       (int64_t)n_out, w.row_skip);
+    THANOS_LAUNCH_CHECK();
+  }
 
   const bool aligned_b = (b % 4 == 0) && (B % 4 == 0);
   {
@@ -973,6 +1064,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.Lam = lam_sb + loff;
     sa.st = w.st;
     sa.st_rw = w.st;
+    sa.row_skip = w.row_skip;
     sa.row_eq = w.row_eq;
     sa.info = info;
     sa.c = c;

@@ -42,14 +42,15 @@ def gpu_factor(H32: np.ndarray, damping: float):
 
 
 def gpu_prune(W: np.ndarray, H32: np.ndarray, *, mode: str, p=0.0, n=0, m=0, B=128, damp=0.01,
-              mask_in=None, cast=False, U=None, xnorm2=None):
+              mask_in=None, cast=False, U=None, xnorm2=None, alpha=0.0):
     """Run thanos_prune_layer; returns (W_hat fp32, mask uint8, info[, W_cast])."""
     c, b = W.shape
     Wd = dev(W)
     Hd = dev(H32.astype(np.float32)) if H32 is not None else None
     keep = []
     o = th.PruneOpts(mode=th.THANOS_UNSTRUCTURED if mode == "unstructured" else th.THANOS_NM,
-                     sparsity=float(p), n=n, m=m, block_size=B, damping=damp)
+                     sparsity=float(p), n=n, m=m, block_size=B, damping=damp,
+                     outlier_fraction=float(alpha))
     if mask_in is not None:
         md = dev(mask_in.astype(np.uint8))
         keep.append(md)

@@ -143,6 +143,63 @@ def test_cfg5_like_block256_heavy_tailed():
     assert (Mg != Mo).mean() < 1e-3
 
 
+# --------------------------------------------------------------------------- outlier rows
+@pytest.mark.parametrize("alpha,n,m,B,use_factor", [(0.1, 2, 4, 128, False), (0.25, 4, 8, 64, True)])
+def test_nm_with_outlier_rows(alpha, n, m, B, use_factor):
+    """n:m algorithm with alpha > 0 (App. G.4.4): the ceil(alpha c) rows of largest loss
+    h_i = W_i H W_i^T stay dense and untouched, the others are pruned as usual."""
+    from tests.gpu_util import gpu_factor, gpu_prune
+    c, b = 200, 384
+    W, H32 = _layer(c, b, 2048, "f16", rho=0.7, seed=21)
+    # spread the row norms: the ranking of the row losses is then decided far above fp32 noise
+    scale = np.linspace(0.5, 2.0, c)[np.random.default_rng(5).permutation(c)]
+    W = (W.astype(np.float64) * scale[:, None]).astype(np.float16)
+    H = H32.astype(np.float64)
+    n_out = orc.num_outlier_rows(alpha, c)
+    h = np.sort(orc.row_losses(W.astype(np.float64), H))
+    assert (h[c - n_out] - h[c - n_out - 1]) / h[c - n_out] > 1e-3   # margin at the cut
+    rows = orc.pruned_rows(W.astype(np.float64), H, alpha)
+    print(f"outlier rows alpha={alpha} {n}:{m} B={B}", flush=True)
+    kw = {}
+    if use_factor:   # H is still needed for the row losses
+        U, xn2, info = gpu_factor(H32, 0.01)
+        assert info == 0
+        kw = dict(U=U, xnorm2=xn2)
+    Wg, Mg, info = gpu_prune(W, H32, mode="nm", n=n, m=m, B=B, alpha=alpha, **kw)
+    assert info == 0
+    # outlier rows: untouched, no mask
+    np.testing.assert_array_equal(Mg[~rows], 0)
+    np.testing.assert_array_equal(Wg[~rows], W[~rows].astype(np.float32))
+    assert (~rows).sum() == n_out
+    # pruned rows: exact n:m pattern, parity with the oracle
+    assert np.all(Mg[rows].reshape(rows.sum(), b // m, m).sum(axis=2) == n)
+    Wo, Mo, mg = orc.prune_nm(W, H, n, m, B, 0.01, return_margins=True, alpha=alpha)
+    diff_rows = np.unique(np.nonzero(Mg != Mo)[0])
+    for i in diff_rows:   # a differing group must be a near-tie in the oracle
+        j = np.nonzero((Mg[i] != Mo[i]).reshape(b // m, m).any(axis=1))[0][0]
+        assert mg[i, j] < 1e-4, (i, j, mg[i, j])
+    assert len(diff_rows) <= 2
+    ok = np.setdiff1d(np.arange(c), diff_rows)
+    assert _rel(Wg[ok], Wo[ok]) < 1e-3
+    Wt, _ = orc.prune_fast(W, H, mode="nm", n=n, m=m, B=B, damp=0.01, mask_in=Mg)
+    assert _rel(Wg, Wt) < 1e-3
+
+
+def test_outlier_rows_argument_checks():
+    import torch
+    import paper_2504_05346_amd as th
+    o = th.PruneOpts(mode=th.THANOS_UNSTRUCTURED, sparsity=0.5, block_size=128, damping=0.01,
+                     outlier_fraction=0.1)
+    assert th.thanos_prune_workspace_bytes(64, 128, o) == 0          # not defined for Alg. 1
+    o = th.PruneOpts(mode=th.THANOS_NM, n=2, m=4, block_size=128, damping=0.01,
+                     outlier_fraction=1.0)
+    assert th.thanos_prune_workspace_bytes(64, 128, o) == 0          # alpha must be < 1
+    o0 = th.PruneOpts(mode=th.THANOS_NM, n=2, m=4, block_size=128, damping=0.01)
+    o1 = th.PruneOpts(mode=th.THANOS_NM, n=2, m=4, block_size=128, damping=0.01,
+                      outlier_fraction=0.1)
+    assert th.thanos_prune_workspace_bytes(64, 128, o1) > th.thanos_prune_workspace_bytes(64, 128, o0)
+
+
 # --------------------------------------------------------------------------- forced masks
 def test_given_mask_with_empty_and_full_rows():
     from tests.gpu_util import gpu_prune
