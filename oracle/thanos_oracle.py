@@ -25,6 +25,9 @@ What is followed
   * n:m sweep:              the n:m algorithm of App. G.4.4; alpha > 0 (outlier rows,
                             Sec. 4.7 "Outlier rows"): row losses h_i = ||W_i X||^2, the
                             ceil(alpha*c) rows with the largest loss are not pruned.
+  * Structured pruning:     Alg. 2 (Sec. 4.7): s = ceil(p*b/(1-alpha)) whole columns, chosen by
+                            the column loss v_j of the non-outlier rows, removed from those
+                            rows in one shot with the full inverse Hessian.
   * Magnitude pruning:      Sec. 3.1 / App. F.1 (comparator for the sanity bound).
 
 Readings taken where the paper is silent or inconsistent (each is listed in the
@@ -285,6 +288,52 @@ def _group_margins(Wblk, xn2blk, n, m, dtype) -> np.ndarray:
     mu = np.sort(metric(Wblk, xn2blk, dtype).reshape(c, width // m, m), axis=2).astype(np.float64)
     lo, hi = mu[:, :, n - 1], mu[:, :, n]
     return (hi - lo) / np.maximum(hi, np.finfo(np.float64).tiny)
+
+
+# --------------------------------------------------------------------------
+# Structured pruning (Alg. 2)
+# --------------------------------------------------------------------------
+def num_columns_to_remove(p, alpha, b: int) -> int:
+    """s = ceil(p*b / (1 - alpha)), evaluated exactly on the decimal values of p and alpha."""
+    pf = Fraction(str(p)) if not isinstance(p, Fraction) else p
+    af = Fraction(str(alpha)) if not isinstance(alpha, Fraction) else alpha
+    if not (0 <= pf < 1 and 0 <= af < 1):
+        raise ValueError("p and alpha must be in [0, 1)")
+    return int(math.ceil(pf * b / (1 - af)))
+
+
+def column_losses(W: np.ndarray, xnorm2: np.ndarray, rows: np.ndarray) -> np.ndarray:
+    """v_j = ||W_{rows, j} (outer) X_j||_F^2 = (sum_{i in rows} W_ij^2) * ||X_j||^2 (Sec. 4.7,
+    eq. (column loss)); `rows` = the rows that are pruned (outlier rows do not count)."""
+    W = np.asarray(W, dtype=np.float64)
+    return (W[rows] ** 2).sum(axis=0) * np.asarray(xnorm2, dtype=np.float64)
+
+
+def prune_structured(W: np.ndarray, H: np.ndarray, p, alpha, damp: float,
+                     dtype=np.float64):
+    """Alg. 2.  Returns (W_hat, M).  No matrix is physically permuted: Q W P of the listing
+    only serves to address the pruned rows (all but the ceil(alpha*c) of largest loss h_i) and
+    the removed columns (the s of smallest loss v_j, ascending (v, j)).  The update is
+    eq. (structured solution), Delta = -W_{:,Q} (Hinv[Q,Q])^{-1} Hinv[Q,:], with Hinv the
+    inverse of the damped Hessian.  `dtype` is the precision in which both rankings are taken.
+    """
+    W = np.array(W, dtype=np.float64, copy=True)
+    c, b = W.shape
+    s = num_columns_to_remove(p, alpha, b)
+    if s > b:
+        raise ValueError("p / (1 - alpha) must not exceed 1")
+    rows = pruned_rows(W, H, alpha, dtype)
+    v = column_losses(W, np.diag(H), rows).astype(dtype)
+    Q = np.sort(np.lexsort((np.arange(b), v))[:s])
+    M = np.zeros((c, b), dtype=np.uint8)
+    if s == 0 or not rows.any():
+        return W, M
+    Hinv = np.linalg.inv(damped(H, damp))
+    lam = np.linalg.solve(Hinv[np.ix_(Q, Q)].T, W[np.ix_(rows, Q)].T).T   # W_Q (Hinv_QQ)^-1
+    W[rows] -= lam @ Hinv[Q, :]
+    W[np.ix_(rows, Q)] = 0.0
+    M[np.ix_(rows, Q)] = 1
+    return W, M
 
 
 # --------------------------------------------------------------------------
