@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--c", type=int, default=4096)
     ap.add_argument("--b", type=int, default=11008)
     ap.add_argument("--tokens", type=int, default=262144)
-    ap.add_argument("--mode", default="nm", choices=["nm", "unstructured"])
+    ap.add_argument("--mode", default="nm", choices=["nm", "unstructured", "structured"])
     ap.add_argument("--n", type=int, default=2)
     ap.add_argument("--m", type=int, default=4)
     ap.add_argument("--sparsity", type=float, default=0.5)
@@ -99,9 +99,12 @@ def cpu_baseline(args, W, X, torch):
     U = orc.inverse_factor(orc.damped(Hs, args.damping))
     t_f = time.perf_counter() - t0
     t0 = time.perf_counter()
-    orc.prune_fast(Ws, Hs, mode=args.mode, p=args.sparsity, n=args.n, m=args.m, B=args.block,
-                   damp=args.damping, U=U,
-                   alpha=args.outlier_fraction if args.mode == "nm" else 0)
+    if args.mode == "structured":
+        orc.prune_structured(Ws, Hs, args.sparsity, args.outlier_fraction, args.damping)
+    else:
+        orc.prune_fast(Ws, Hs, mode=args.mode, p=args.sparsity, n=args.n, m=args.m, B=args.block,
+                       damp=args.damping, U=U,
+                       alpha=args.outlier_fraction if args.mode == "nm" else 0)
     t_s = time.perf_counter() - t0
     est = t_h * (args.tokens / tok_s) + t_f + t_s * (args.c / rows_s)
     return {
@@ -134,7 +137,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     c, b, T = args.c, args.b, args.tokens
-    o = th.PruneOpts(mode=th.THANOS_NM if args.mode == "nm" else th.THANOS_UNSTRUCTURED,
+    o = th.PruneOpts(mode={"nm": th.THANOS_NM, "unstructured": th.THANOS_UNSTRUCTURED,
+                           "structured": th.THANOS_STRUCTURED}[args.mode],
                      sparsity=args.sparsity, n=args.n, m=args.m, block_size=args.block,
                      damping=args.damping, outlier_fraction=args.outlier_fraction)
     nbytes = th.thanos_prune_workspace_bytes(c, b, o)
@@ -181,7 +185,7 @@ def main():
 
     kept = int((M == 0).sum().item())
     workload = (f"{c}x{b} fp16 layer, {T} fp16 calibration tokens, "
-                + (f"{args.n}:{args.m}" if args.mode == "nm" else f"{args.sparsity:g} unstructured")
+                + (f"{args.n}:{args.m}" if args.mode == "nm" else f"{args.sparsity:g} {args.mode}")
                 + f", block {args.block}, damping {args.damping:g}"
                 + (f", outlier rows {args.outlier_fraction:g}" if args.outlier_fraction else ""))
     out = {

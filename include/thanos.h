@@ -43,11 +43,15 @@ typedef enum {
 } thanos_status;
 
 typedef enum { THANOS_F32 = 0, THANOS_F16 = 1, THANOS_BF16 = 2 } thanos_dtype;
-typedef enum { THANOS_UNSTRUCTURED = 0, THANOS_NM = 1 } thanos_mode;
+typedef enum { THANOS_UNSTRUCTURED = 0, THANOS_NM = 1, THANOS_STRUCTURED = 2 } thanos_mode;
 
 /* Options of the block sweep (host struct, read during the call only). */
 typedef struct {
-  int32_t mode;       /* THANOS_UNSTRUCTURED (Alg. 1) or THANOS_NM (n:m algorithm, App. G.4.4) */
+  int32_t mode;       /* THANOS_UNSTRUCTURED (Alg. 1), THANOS_NM (n:m algorithm, App. G.4.4) or
+                         THANOS_STRUCTURED (Alg. 2: ceil(p*b/(1-alpha)) whole columns, those
+                         of smallest loss v_j = (sum_i W_ij^2) H_jj over the non-outlier rows,
+                         are removed from the non-outlier rows in one shot with the full
+                         inverse Hessian; block_size, mask_in unused, factor_in rejected)       */
   double sparsity;    /* p in [0,1): r = floor(p*c*b) weights are removed (Alg. 1, problem
                          statement eq. (2)); p is read as the decimal it prints as, so 0.6
                          means 6/10.  Ignored for THANOS_NM.                                  */
@@ -64,8 +68,9 @@ typedef struct {
   double outlier_fraction; /* alpha in [0,1) of the n:m algorithm (App. G.4.4, Sec. 4.7 "Outlier
                               rows"): the ceil(alpha*c) rows with the largest loss
                               h_i = ||W_i X||^2 = W_i H W_i^T are left untouched (dense, mask 0);
-                              ties by row index.  0 = prune every row.  THANOS_NM only; needs H
-                              (undamped) even when factor_in is given.                          */
+                              ties by row index.  0 = prune every row.  THANOS_NM and
+                              THANOS_STRUCTURED; needs H (undamped) even when factor_in is
+                              given.                                                            */
 } thanos_prune_opts;
 
 /*

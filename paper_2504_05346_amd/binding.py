@@ -14,7 +14,7 @@ from typing import Optional
 import torch  # noqa: F401  (imported first so that the HIP runtime torch ships is the one in use)
 
 THANOS_F32, THANOS_F16, THANOS_BF16 = 0, 1, 2
-THANOS_UNSTRUCTURED, THANOS_NM = 0, 1
+THANOS_UNSTRUCTURED, THANOS_NM, THANOS_STRUCTURED = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(_HERE, "libthanos.so")

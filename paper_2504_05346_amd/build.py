@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libthanos.so")
-SOURCES = ["api.hip", "syrk.hip", "gemm_f32.hip", "factor.hip", "sweep.hip"]
+SOURCES = ["api.hip", "syrk.hip", "gemm_f32.hip", "factor.hip", "sweep.hip", "structured.hip"]
 HEADERS = ["common.h", "gemm_tile.h", "gemm_tile_x3.h", os.path.join("..", "..", "include", "thanos.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -4,14 +4,15 @@
 #include "common.h"
 
 namespace thanos {
-size_t factor_workspace_bytes(int64_t b);
-thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
-                     float* xnorm2, void* ws, int32_t* info);
 size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers);
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
                     void* W_cast, uint8_t* mask, void* ws, int32_t* info);
+size_t structured_workspace_bytes(int64_t c, int64_t b);
+thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                         const float* H, float damping, long long s_cols, long long n_out,
+                         float* W, void* W_cast, uint8_t* mask, void* ws, int32_t* info);
 __global__ void k_zero_info(int32_t* info) { *info = 0; }
 }  // namespace thanos
 
@@ -38,11 +39,29 @@ static long long num_outlier_rows(double alpha, int64_t c) {
   return n < 0 ? 0 : (n > c ? c : n);
 }
 
+// Columns removed by the structured algorithm, ceil(p*b/(1-alpha)), decimals as above.
+static long long num_columns_to_remove(double p, double alpha, int64_t b) {
+  const long double x = (long double)p * (long double)b / (1.0L - (long double)alpha);
+  long long n = (long long)ceill(x);
+  if (x - (long double)(n - 1) < 1e-6L) n -= 1;
+  return n < 0 ? 0 : n;
+}
+
 static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b) {
   if (!o) return THANOS_ERR_INVALID_ARG;
-  if (o->mode != THANOS_UNSTRUCTURED && o->mode != THANOS_NM) return THANOS_ERR_INVALID_ARG;
-  if (o->block_size < 1) return THANOS_ERR_INVALID_ARG;
+  if (o->mode != THANOS_UNSTRUCTURED && o->mode != THANOS_NM && o->mode != THANOS_STRUCTURED)
+    return THANOS_ERR_INVALID_ARG;
   if (!(o->damping >= 0.f)) return THANOS_ERR_INVALID_ARG;
+  if (!(o->outlier_fraction >= 0.0 && o->outlier_fraction < 1.0)) return THANOS_ERR_INVALID_ARG;
+  if (o->mode == THANOS_STRUCTURED) {
+    if (!(o->sparsity >= 0.0 && o->sparsity < 1.0)) return THANOS_ERR_INVALID_ARG;
+    if (num_columns_to_remove(o->sparsity, o->outlier_fraction, b) > b)
+      return THANOS_ERR_INVALID_ARG;  // p / (1 - alpha) > 1
+    if (o->factor_in || o->mask_in) return THANOS_ERR_UNSUPPORTED;  // the factor is of H[sigma,sigma]
+    (void)c;
+    return THANOS_OK;
+  }
+  if (o->block_size < 1) return THANOS_ERR_INVALID_ARG;
   if (o->mode == THANOS_UNSTRUCTURED) {
     if (!(o->sparsity >= 0.0 && o->sparsity < 1.0)) return THANOS_ERR_INVALID_ARG;
   } else {
@@ -51,7 +70,6 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
     if (o->m > 16) return THANOS_ERR_UNSUPPORTED;
   }
   if (o->factor_in && !o->xnorm2_in) return THANOS_ERR_INVALID_ARG;
-  if (!(o->outlier_fraction >= 0.0 && o->outlier_fraction < 1.0)) return THANOS_ERR_INVALID_ARG;
   if (o->outlier_fraction > 0.0 && o->mode != THANOS_NM) return THANOS_ERR_UNSUPPORTED;
   if (o->block_size > 256) return THANOS_ERR_UNSUPPORTED;
   (void)c;
@@ -98,6 +116,7 @@ thanos_status thanos_factor(const float* H, int64_t b, float damping, float* U, 
 
 size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opts* opts) {
   if (c <= 0 || b <= 0 || check_opts(opts, c, b) != THANOS_OK) return 0;
+  if (opts->mode == THANOS_STRUCTURED) return structured_workspace_bytes(c, b);
   size_t n = sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
   if (!opts->factor_in) {
     n += align_up((size_t)b * b * sizeof(float), 256);  // U
@@ -121,6 +140,13 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
   if (!ws || ws_bytes < thanos_prune_workspace_bytes(c, b, opts)) return THANOS_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  if (opts->mode == THANOS_STRUCTURED) {
+    if (!H) return THANOS_ERR_INVALID_ARG;
+    return structured(s, W_in, wdt, c, b, H, opts->damping,
+                      num_columns_to_remove(opts->sparsity, opts->outlier_fraction, b),
+                      num_outlier_rows(opts->outlier_fraction, c), W_out, W_out_cast, mask_out, ws,
+                      info_dev);
+  }
 
   char* p = reinterpret_cast<char*>(ws);
   void* sweep_ws = p;

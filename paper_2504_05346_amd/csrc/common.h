@@ -71,4 +71,16 @@ thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, i
 thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc,
                               thanos_dtype xdt, int64_t n_tok, int64_t ldx, float alpha);
 
+// Damped factorisation (factor.hip).  After it the lower triangle of the reversed, padded copy
+// in the workspace holds the Cholesky factor L of J H_d J (U = J L^{-1} J): factor_L() returns
+// it and its leading dimension.
+size_t factor_workspace_bytes(int64_t b);
+thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
+                     float* xnorm2, void* ws, int32_t* info);
+const float* factor_L(const void* ws, int64_t b, int64_t* ld);
+
+// skip[i] = 1 for the n_out rows of W (c x b fp32) with the largest loss W_i H W_i^T (sweep.hip).
+thanos_status row_outliers(hipStream_t s, const float* W, const float* H, int64_t c, int64_t b,
+                           long long n_out, float* Hf, float* T, float* h, uint8_t* skip);
+
 }  // namespace thanos

@@ -463,6 +463,11 @@ __global__ __launch_bounds__(256) void k_reverse_out(const float* __restrict__ L
 
 static inline int64_t padded(int64_t b) { return ceil_div(b, NB) * NB; }
 
+const float* factor_L(const void* ws, int64_t b, int64_t* ld) {
+  *ld = padded(b);
+  return reinterpret_cast<const float*>(reinterpret_cast<const char*>(ws) + 256);
+}
+
 size_t factor_workspace_bytes(int64_t b) {
   const int64_t bp = padded(b);
   return 3 * (size_t)bp * bp * sizeof(float) + 256;

@@ -883,6 +883,23 @@ __global__ __launch_bounds__(256) void k_row_rank(const float* __restrict__ h, i
   skip[i] = rank >= c - n_out ? 1 : 0;
 }
 
+// skip[i] = 1 for the n_out rows of W (c x b fp32) with the largest loss W_i H W_i^T (H: lower
+// triangle).  Hf (b x b), T (c x b) and h (c) are scratch.
+thanos_status row_outliers(hipStream_t s, const float* W, const float* H, int64_t c, int64_t b,
+                           long long n_out, float* Hf, float* T, float* h, uint8_t* skip) {
+  hipLaunchKernelGGL(k_mirror_lower, dim3((unsigned)ceil_div(b, 32), (unsigned)ceil_div(b, 32)),
+                     dim3(256), 0, s, H, b, Hf);
+  THANOS_LAUNCH_CHECK();
+  thanos_status st = gemm_f32(s, false, true, c, b, b, 1.f, W, b, Hf, b, 0.f, T, b, false);
+  if (st != THANOS_OK) return st;
+  hipLaunchKernelGGL(k_rowdot, dim3((unsigned)ceil_div(c, 4)), dim3(256), 0, s, T, W, c, b, h);
+  THANOS_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_row_rank, dim3((unsigned)ceil_div(c, 256)), dim3(256), 0, s, h, c,
+                     (int64_t)n_out, skip);
+  THANOS_LAUNCH_CHECK();
+  return THANOS_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 struct SweepWs {
   float* sx;
@@ -996,16 +1013,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   hipLaunchKernelGGL(k_sqrt, dim3((unsigned)ceil_div(b, 256)), dim3(256), 0, s, xnorm2, w.sx, b);
   THANOS_LAUNCH_CHECK();
   if (outliers) {
-    hipLaunchKernelGGL(k_mirror_lower, dim3((unsigned)ceil_div(b, 32), (unsigned)ceil_div(b, 32)),
-                       dim3(256), 0, s, H, b, w.Hf);
-    THANOS_LAUNCH_CHECK();
-    thanos_status st = gemm_f32(s, false, true, c, b, b, 1.f, W, b, w.Hf, b, 0.f, w.T, b, false);
+    thanos_status st = row_outliers(s, W, H, c, b, n_out, w.Hf, w.T, w.h, w.row_skip);
     if (st != THANOS_OK) return st;
-    hipLaunchKernelGGL(k_rowdot, dim3((unsigned)ceil_div(c, 4)), dim3(256), 0, s, w.T, W, c, b, w.h);
-    THANOS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_row_rank, dim3((unsigned)ceil_div(c, 256)), dim3(256), 0, s, w.h, c,
-                       (int64_t)n_out, w.row_skip);
-    THANOS_LAUNCH_CHECK();
   }
 
   const bool aligned_b = (b % 4 == 0) && (B % 4 == 0);

@@ -48,7 +48,8 @@ def gpu_prune(W: np.ndarray, H32: np.ndarray, *, mode: str, p=0.0, n=0, m=0, B=1
     Wd = dev(W)
     Hd = dev(H32.astype(np.float32)) if H32 is not None else None
     keep = []
-    o = th.PruneOpts(mode=th.THANOS_UNSTRUCTURED if mode == "unstructured" else th.THANOS_NM,
+    o = th.PruneOpts(mode={"unstructured": th.THANOS_UNSTRUCTURED, "nm": th.THANOS_NM,
+                           "structured": th.THANOS_STRUCTURED}[mode],
                      sparsity=float(p), n=n, m=m, block_size=B, damping=damp,
                      outlier_fraction=float(alpha))
     if mask_in is not None:
