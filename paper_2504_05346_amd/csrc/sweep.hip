@@ -126,8 +126,16 @@ struct SelState {
   long long need_eq;    // how many keys equal to tau are removed (ties, in (row, col) order)
   unsigned int prefix;  // resolved high bits
   unsigned int tau;     // r-th smallest key
-  int blk_count;        // weights removed in the block just finished
   int none;             // 1: nothing left to remove
+  // prediction from the previous block: the threshold moves little from block to block (a few
+  // thousand key values at the headline shape), so one pass that histograms a window of
+  // 2048 x 16 keys around the previous tau (and counts what lies below it) usually replaces the
+  // first two radix passes and leaves 4 bits to the last one
+  unsigned long long below;  // keys below the window
+  unsigned int win_lo;       // first 28-bit prefix (key >> 4) of the window
+  int pred_try;              // 1: a previous tau exists
+  int pred_ok;               // 1: the rank fell inside the window, prefix holds 28 bits
+  int shift;                 // low bits left to the last pass: 10, or 4 after a window hit
 };
 
 __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
@@ -137,17 +145,18 @@ __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
 // One wavefront per row; lanes stride over the residual columns (16 bytes per lane when the
 // row segment is 16-byte aligned, so that a wavefront keeps 1 KB per load instruction in flight).
 // PASS 0: bin = key >> 21.  PASS 1: keys with key>>21 == prefix, bin = (key>>10) & 2047.
-// PASS 2: keys with key>>10 == prefix, bin = key & 1023; also counts those keys per row.
+// PASS 2: keys with key>>shift == prefix, bin = the low `shift` bits (10, or 4 after a window hit);
+// also counts those keys per row.
 template <int PASS>
 __device__ __forceinline__ void sel_count(unsigned int* h, unsigned int key, unsigned int prefix,
-                                          int& cand) {
+                                          int shift, int& cand) {
   if (PASS == 0) {
     atomicAdd(&h[key >> 21], 1u);
   } else if (PASS == 1) {
     if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
   } else {
-    if ((key >> 10) == prefix) {
-      atomicAdd(&h[key & 1023u], 1u);
+    if ((key >> shift) == prefix) {
+      atomicAdd(&h[key & ((1u << shift) - 1u)], 1u);
       ++cand;
     }
   }
@@ -161,10 +170,12 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
                                                   int* __restrict__ row_cand, int vec) {
   __shared__ unsigned int h[2048];
   if (st->none) return;
+  if (PASS < 2 && st->pred_ok) return;  // the window pass already resolved 22 bits
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int e = tid; e < 2048; e += 256) h[e] = 0u;
   __syncthreads();
   const unsigned int prefix = st->prefix;
+  const int shift = st->shift;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave;
   if (i < c) {
     const float* row = W + i * b;
@@ -175,16 +186,16 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
         const int64_t j = j1 + 4 * v;
         const float4 w4 = *reinterpret_cast<const float4*>(row + j);
         const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
-        sel_count<PASS>(h, metric_key(w4.x, s4.x), prefix, cand);
-        sel_count<PASS>(h, metric_key(w4.y, s4.y), prefix, cand);
-        sel_count<PASS>(h, metric_key(w4.z, s4.z), prefix, cand);
-        sel_count<PASS>(h, metric_key(w4.w, s4.w), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.x, s4.x), prefix, shift, cand);
+        sel_count<PASS>(h, metric_key(w4.y, s4.y), prefix, shift, cand);
+        sel_count<PASS>(h, metric_key(w4.z, s4.z), prefix, shift, cand);
+        sel_count<PASS>(h, metric_key(w4.w, s4.w), prefix, shift, cand);
       }
       for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64)
-        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, cand);
+        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, shift, cand);
     } else {
       for (int64_t j = j1 + lane; j < b; j += 64)
-        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, cand);
+        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, shift, cand);
     }
     if (PASS == 2) {
       for (int off = 32; off > 0; off >>= 1) cand += __shfl_down(cand, off, 64);
@@ -197,12 +208,146 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
 }
 
 // Start of a block: r <- r - ||M||_F^2 of the previous block (Alg. 1), reset the search.
-__global__ void k_sel_begin(SelState* __restrict__ st) {
-  st->r_rem -= st->blk_count;
-  st->blk_count = 0;
+// (row_cnt[i] = weights the previous block removed from row i; one array entry per row instead
+// of thousands of atomics on one counter.)
+__global__ __launch_bounds__(256) void k_sel_begin(SelState* __restrict__ st, int first,
+                                                   const int* __restrict__ row_cnt, int64_t c) {
+  __shared__ long long part[256];
+  const int tid = threadIdx.x;
+  long long sum = 0;
+  if (!first)
+    for (int64_t i = tid; i < c; i += 256) sum += row_cnt[i];
+  part[tid] = sum;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (tid < off) part[tid] += part[tid + off];
+    __syncthreads();
+  }
+  if (tid != 0) return;
+  st->r_rem -= part[0];
   st->rank = st->r_rem;
   st->prefix = 0u;
   st->none = (st->r_rem <= 0) ? 1 : 0;
+  const unsigned int p28 = st->tau >> 4;
+  st->pred_try = (!first && st->tau != 0u) ? 1 : 0;
+  st->win_lo = p28 > 1024u ? p28 - 1024u : 0u;
+  st->below = 0ull;
+  st->pred_ok = 0;
+  st->shift = 10;
+}
+
+// Window pass: bin = (key >> 4) - win_lo for the 2048 prefixes of the window, keys below the
+// window are counted, keys above it ignored.  Few keys fall inside, so most wavefront
+// iterations skip the LDS atomics and the pass runs at memory speed.
+__global__ __launch_bounds__(256) void k_sel_win(const float* __restrict__ W, int64_t c, int64_t b,
+                                                 int64_t j1, const float* __restrict__ sx,
+                                                 const SelState* __restrict__ st,
+                                                 unsigned int* __restrict__ hist,
+                                                 unsigned int* __restrict__ below_part, int vec) {
+  __shared__ unsigned int h[2048];
+  __shared__ unsigned int nb_wave[4];
+  if (st->none || !st->pred_try) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int e = tid; e < 2048; e += 256) h[e] = 0u;
+  __syncthreads();
+  const unsigned int lo = st->win_lo;
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+  if (i < c) {
+    const float* row = W + i * b;
+    unsigned int nb = 0;
+    auto count = [&](unsigned int key) {
+      const unsigned int p28 = key >> 4;
+      if (p28 < lo) ++nb;
+      else if (p28 - lo < 2048u) atomicAdd(&h[p28 - lo], 1u);
+    };
+    if (vec) {
+      const int64_t nvec = (b - j1) >> 2;
+      for (int64_t v = lane; v < nvec; v += 64) {
+        const int64_t j = j1 + 4 * v;
+        const float4 w4 = *reinterpret_cast<const float4*>(row + j);
+        const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
+        count(metric_key(w4.x, s4.x));
+        count(metric_key(w4.y, s4.y));
+        count(metric_key(w4.z, s4.z));
+        count(metric_key(w4.w, s4.w));
+      }
+      for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64) count(metric_key(row[j], sx[j]));
+    } else {
+      for (int64_t j = j1 + lane; j < b; j += 64) count(metric_key(row[j], sx[j]));
+    }
+    for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
+    if (lane == 0) nb_wave[wave] = nb;
+  } else if (lane == 0) {
+    nb_wave[wave] = 0u;
+  }
+  __syncthreads();
+  // one partial count per workgroup (summed by the scan): thousands of atomics on one
+  // address would cost more than the pass itself
+  if (tid == 0) below_part[blockIdx.x] = nb_wave[0] + nb_wave[1] + nb_wave[2] + nb_wave[3];
+  for (int e = tid; e < 2048; e += 256)
+    if (h[e]) atomicAdd(&hist[e], h[e]);
+}
+
+// If the rank lies inside the window: 28 bits of the key are resolved, the first two radix
+// passes are skipped and the last one resolves 4 bits.  Otherwise nothing is changed and all
+// three run.
+__global__ __launch_bounds__(256) void k_sel_scan_win(SelState* __restrict__ st,
+                                                      unsigned int* __restrict__ hist,
+                                                      const unsigned int* __restrict__ below_part,
+                                                      int n_part) {
+  __shared__ long long part[256];
+  __shared__ int sel_bin;
+  __shared__ long long sel_before;
+  const int tid = threadIdx.x;
+  if (st->none || !st->pred_try) return;
+  long long bsum = 0;
+  for (int e = tid; e < n_part; e += 256) bsum += below_part[e];
+  part[tid] = bsum;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (tid < off) part[tid] += part[tid + off];
+    __syncthreads();
+  }
+  const long long below = part[0];
+  __syncthreads();
+  if (tid == 0) st->below = (unsigned long long)below;
+  const long long rank = st->rank - below;  // rank inside the window
+  unsigned int loc[8];
+  long long s = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    loc[e] = hist[tid * 8 + e];
+    s += loc[e];
+  }
+  part[tid] = s;
+  if (tid == 0) sel_bin = -1;
+  __syncthreads();
+  if (tid == 0) {
+    long long run = 0;
+    for (int t = 0; t < 256; ++t) {
+      const long long v = part[t];
+      part[t] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  long long before = part[tid];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (rank > 0 && before < rank && rank <= before + loc[e]) {
+      sel_bin = tid * 8 + e;
+      sel_before = before;
+    }
+    before += loc[e];
+  }
+  __syncthreads();
+  if (tid == 0 && sel_bin >= 0) {
+    st->prefix = st->win_lo + (unsigned int)sel_bin;
+    st->rank = rank - sel_before;
+    st->pred_ok = 1;
+    st->shift = 4;
+  }
+  for (int e = tid; e < 2048; e += 256) hist[e] = 0u;
 }
 
 template <int PASS>
@@ -213,6 +358,7 @@ __global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
   __shared__ long long sel_before;
   const int tid = threadIdx.x;
   if (st->none) return;  // the histogram passes did not run either
+  if (PASS < 2 && st->pred_ok) return;
   const long long rank = st->rank;
   unsigned int loc[8];
   long long s = 0;
@@ -243,7 +389,7 @@ __global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
   }
   __syncthreads();
   if (tid == 0) {
-    const int bits = (PASS == 2) ? 10 : 11;
+    const int bits = (PASS == 2) ? st->shift : 11;
     st->prefix = (st->prefix << bits) | (unsigned int)sel_bin;
     st->rank = rank - sel_before;
     if (PASS == 2) {
@@ -254,7 +400,7 @@ __global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
   for (int e = tid; e < 2048; e += 256) hist[e] = 0u;
 }
 
-// Ties: rows that hold candidates (keys sharing tau's upper 22 bits) count their keys equal to
+// Ties: rows that hold candidates (keys sharing the bits of tau resolved before the last pass) count their keys equal to
 // tau over the residual row; other rows have none.
 __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, int64_t c, int64_t b,
                                                   int64_t j1, const float* __restrict__ sx,
@@ -340,6 +486,7 @@ struct SolveArgs {
   const SelState* st;    // SEL_THRESHOLD
   SelState* st_rw;
   const int* row_eq;     // exclusive tie prefix per row
+  int* row_cnt;          // SEL_THRESHOLD: number of weights removed from row i in this block
   const uint8_t* row_skip;  // optional, c bytes: 1 = row is left untouched (outlier row)
   int32_t* info;
   int64_t c, b, j1;
@@ -420,7 +567,7 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
   if (sel) q[myrank] = tid;
   if (tid < a.bw) a.mask_out[i * a.b + a.j1 + tid] = sel ? 1 : 0;
   if (SEL == SEL_THRESHOLD) {
-    if (tid == 0 && s > 0) atomicAdd(&a.st_rw->blk_count, s);
+    if (tid == 0) a.row_cnt[i] = s;  // summed at the start of the next block
   }
   float* lam_g = a.Lam + i * a.ldl;
   if (s == 0) {
@@ -627,7 +774,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
     if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[r] ? 1 : 0;
   }
   if (SEL == SEL_THRESHOLD) {
-    if (lane == 0 && s > 0) atomicAdd(&a.st_rw->blk_count, s);
+    if (lane == 0) a.row_cnt[i] = s;  // summed at the start of the next block
   }
   float* lam_g = a.Lam + i * a.ldl;
   if (s == 0 || s > 64) {  // s > 64 cannot happen for a launch chosen by the host
@@ -971,8 +1118,12 @@ __global__ void k_init_state(SelState* st, long long r) {
   st->need_eq = 0;
   st->prefix = 0u;
   st->tau = 0u;
-  st->blk_count = 0;
   st->none = (r <= 0) ? 1 : 0;
+  st->below = 0ull;
+  st->win_lo = 0u;
+  st->pred_try = 0;
+  st->pred_ok = 0;
+  st->shift = 10;
 }
 
 template <int SEL>
@@ -1062,7 +1213,13 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       // 16-byte loads need W + i*b + j1 and sx + j1 aligned (W, sx come 256-byte aligned)
       const int sel_vec = (b % 4 == 0 && j1 % 4 == 0 &&
                            reinterpret_cast<uintptr_t>(W) % 16 == 0) ? 1 : 0;
-      hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(1), 0, s, w.st);
+      hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(256), 0, s, w.st, j1 == 0 ? 1 : 0, w.row_cand, c);
+      if (j1 > 0) {
+        hipLaunchKernelGGL(k_sel_win, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st, w.hist,
+                           reinterpret_cast<unsigned int*>(w.row_cand), sel_vec);
+        hipLaunchKernelGGL(k_sel_scan_win, dim3(1), dim3(256), 0, s, w.st, w.hist,
+                           reinterpret_cast<const unsigned int*>(w.row_cand), (int)rows4);
+      }
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
                          w.hist, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_sel_scan<0>, dim3(1), dim3(256), 0, s, w.st, w.hist);
@@ -1088,6 +1245,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.st_rw = w.st;
     sa.row_skip = w.row_skip;
     sa.row_eq = w.row_eq;
+    sa.row_cnt = w.row_cand;  // free once k_tie_rows has read the candidate flags
     sa.info = info;
     sa.c = c;
     sa.b = b;
