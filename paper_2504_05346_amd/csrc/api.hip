@@ -71,7 +71,12 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
   }
   if (o->factor_in && !o->xnorm2_in) return THANOS_ERR_INVALID_ARG;
   if (o->outlier_fraction > 0.0 && o->mode != THANOS_NM) return THANOS_ERR_UNSUPPORTED;
-  if (o->block_size > 256) return THANOS_ERR_UNSUPPORTED;
+  // the per-row systems must fit the solver: at most 256 unknowns, blocks of at most 512 columns
+  if (o->mode == THANOS_NM && !o->mask_in) {
+    if (o->block_size > 512 || o->block_size / o->m * o->n > 256) return THANOS_ERR_UNSUPPORTED;
+  } else if (o->block_size > 256) {
+    return THANOS_ERR_UNSUPPORTED;
+  }
   (void)c;
   return THANOS_OK;
 }

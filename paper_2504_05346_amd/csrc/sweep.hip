@@ -491,6 +491,7 @@ struct SolveArgs {
   int32_t* info;
   int64_t c, b, j1;
   int bw, ldl, n, m;
+  int nt_lo, nt_max;     // k_solve_tiled: rows with nt_lo <= ceil(s/32) <= nt_max; LDS holds nt_max
 };
 
 // ------------------------------------------------------------------------------------------
@@ -920,6 +921,349 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Mask + per-row solve for systems of 65..256 unknowns (block width <= 512): one workgroup of
+// four wavefronts per row of W.  R_hat = G[q, q] is held in LDS as the lower triangle of a grid
+// of 32x32 tiles (padded with the identity past s) and factored by a right-looking blocked
+// Cholesky, R_hat = L L^T, 32 columns per step:
+//   1. one wavefront eliminates the diagonal tile with rank-1 MFMAs on its accumulator-layout
+//      copy (row k of a symmetric tile is both operands of D -= u u^T / d) and carries a second
+//      tile that starts as I along, which ends as T = L_pp^{-1}; T replaces the diagonal tile;
+//   2. the tiles below it become L_ip = A_ip T^T (one 32x32x32 product each), y_p = T u_p;
+//   3. the tiles right of the panel get A_il -= L_ip L_lp^T, the right-hand side u_i -= L_ip y_p.
+// L^T lambda = y is then solved from the last tile row upwards with the same T tiles.
+// All products are fp32 MFMAs (v_mfma_f32_32x32x2_f32) on operands read from LDS.
+constexpr int kTlLd = 33;          // LDS row stride of a tile (conflict-free rows and columns)
+constexpr int kTlSz = 32 * kTlLd;  // floats per tile
+constexpr int kTlSmax = 256;       // largest system
+constexpr int kTlBw = 512;         // widest block
+constexpr int kTlExtra = 3 * kTlSmax + 128 + 16;  // u, lambda, q, pivot scratch, counters
+
+__host__ __device__ inline int tl_ntiles(int nt) { return nt * (nt + 1) / 2; }
+static inline size_t tl_smem_bytes(int nt) {
+  return ((size_t)tl_ntiles(nt) * kTlSz + kTlExtra) * sizeof(float);
+}
+__device__ __forceinline__ int tl_row(int r, int hi) { return 8 * (r >> 2) + 4 * hi + (r & 3); }
+__device__ __forceinline__ float* tl_tile(float* tiles, int i, int j) {
+  return tiles + (i * (i + 1) / 2 + j) * kTlSz;
+}
+// acc += sign * A * Bn^T for 32x32 tiles, A[m][k] at pa[m*kTlLd + k], Bn[n][k] at pb[n*kTlLd + k]
+__device__ __forceinline__ void tl_mma(f32x16& acc, const float* pa, const float* pb, float sign,
+                                       int lo, int hi) {
+  float av[16], bv[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    av[e] = pa[lo * kTlLd + 2 * e + hi];
+    bv[e] = pb[lo * kTlLd + 2 * e + hi];
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e)
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(sign * av[e], bv[e], acc, 0, 0, 0);
+}
+// Eliminates the symmetric tile at Dt and overwrites it with T = L^{-1} (lower triangular, zeros
+// above the diagonal), L its Cholesky factor.  One wavefront.  Returns true if a pivot was not
+// positive.
+__device__ __forceinline__ bool tl_pivots(float* Dt, float* aux, int lo, int hi) {
+  f32x16 D, E;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    D[r] = Dt[tl_row(r, hi) * kTlLd + lo];
+    E[r] = (tl_row(r, hi) == lo) ? 1.f : 0.f;
+  }
+  const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
+  float dl = 1.f;  // pivot of column lo
+#pragma unroll
+  for (int k = 0; k < 32; ++k) {
+    const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(D[rk]), k + 32 * hk));
+    const float rd = __builtin_amdgcn_rcpf(d);
+    const float rdr = fmaf(fmaf(-d, rd, 1.f), rd, rd);
+    const float u = (key[hk] >= k) ? D[rk] : 0.f;  // row k = column k of the reduced tile
+    const float au = -rdr * u;
+    D = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, D, 0, 0, 0);
+    dl = (lo == k) ? d : dl;
+    const float ek = (key[hk] >= 0) ? E[rk] : 0.f;  // T~[k][:]
+    const float a2 = (lo == k) ? 0.f : au;          // row k itself stays
+    E = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, ek, E, 0, 0, 0);
+  }
+  const bool bad = __ballot(!(dl > 0.f)) != 0ull;
+  float isd = __builtin_amdgcn_rsqf(dl);
+  isd = fmaf(0.5f * isd, fmaf(-dl * isd, isd, 1.f), isd);
+  aux[lo] = isd;  // both halves write the same value
+#pragma unroll
+  for (int r = 0; r < 16; ++r)  // L^{-1} = diag(1/sqrt(d)) T~
+    Dt[tl_row(r, hi) * kTlLd + lo] = E[r] * aux[tl_row(r, hi)];
+  return bad;
+}
+
+template <int SEL>
+__global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char solve_smem[];
+  float* tiles = reinterpret_cast<float*>(solve_smem);
+  float* xtra = tiles + tl_ntiles(a.nt_max) * kTlSz;
+  float* u = xtra;                    // right-hand side, then y
+  float* lam = xtra + kTlSmax;
+  int* q = reinterpret_cast<int*>(xtra + 2 * kTlSmax);
+  float* aux = xtra + 3 * kTlSmax;
+  int* cnt = reinterpret_cast<int*>(aux + 128);  // [2][4] selected, [2][4] ties
+  int* eqc = cnt + 8;
+  // the block's weights and metric live in the tile area until the gather overwrites them, and
+  // the lambda row is assembled there after the solve (nt_max >= 3: room for 2 * kTlBw floats)
+  float* wrow = tiles;
+  float* key = tiles + kTlBw;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lo = lane & 31, hi = lane >> 5;
+  const int64_t i = blockIdx.x;
+  const float* wrow_g = a.W + i * a.b + a.j1;
+#ifdef TL_DEBUG
+  long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long tlast = wall_clock64();
+#define TL_MARK(x) do { const long long t_ = wall_clock64(); tph[x] += t_ - tlast; tlast = t_; } while (0)
+#else
+#define TL_MARK(x) do {} while (0)
+#endif
+
+  // ---- selection of the block mask row M_i: column col = tid + 256 * ch ----
+  bool sel[2];
+  float wv[2];
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch) {
+    const int col = tid + 256 * ch;
+    wv[ch] = (col < a.bw) ? wrow_g[col] : 0.f;
+    wrow[col] = wv[ch];
+    sel[ch] = false;
+  }
+  if (SEL == SEL_GIVEN) {
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const int col = tid + 256 * ch;
+      sel[ch] = (col < a.bw) && a.mask_in[i * a.b + a.j1 + col] != 0;
+    }
+  } else if (SEL == SEL_NM) {
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const int col = tid + 256 * ch;
+      key[col] = (col < a.bw) ? fabsf(wv[ch]) * a.sx[a.j1 + col] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const int col = tid + 256 * ch;
+      if (col < a.bw) {
+        const int g0 = (col / a.m) * a.m;
+        const float mine = key[col];
+        int rank = 0;
+        for (int e = 0; e < a.m; ++e) {
+          const float o = key[g0 + e];
+          rank += (o < mine || (o == mine && g0 + e < col)) ? 1 : 0;
+        }
+        sel[ch] = rank < a.n;
+      }
+    }
+    if (a.row_skip && a.row_skip[i]) sel[0] = sel[1] = false;
+  } else {  // SEL_THRESHOLD: key < tau, or key == tau and among the first need_eq ties
+    const bool none = a.st->none != 0;
+    const unsigned int tau = a.st->tau;
+    const long long need_eq = a.st->need_eq;
+    bool lt[2], eq[2];
+    unsigned long long eqb[2];
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const int col = tid + 256 * ch;
+      const bool in = (col < a.bw) && !none;
+      const unsigned int kk = in ? metric_key(wv[ch], a.sx[a.j1 + col]) : 0xffffffffu;
+      lt[ch] = in && kk < tau;
+      eq[ch] = in && kk == tau;
+      eqb[ch] = __ballot(eq[ch]);
+      if (lane == 0) eqc[4 * ch + wave] = __popcll(eqb[ch]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      long long my = a.row_eq[i];
+      for (int v = 0; v < 4 * ch + wave; ++v) my += eqc[v];
+      my += __popcll(eqb[ch] & ((1ull << lane) - 1ull));
+      sel[ch] = lt[ch] || (eq[ch] && my < need_eq);
+    }
+  }
+
+  // ---- q = phi(M_i) (ascending column indices) and s ----
+  unsigned long long bal[2];
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch) {
+    bal[ch] = __ballot(sel[ch]);
+    if (lane == 0) cnt[4 * ch + wave] = __popcll(bal[ch]);
+  }
+  __syncthreads();
+  int s = 0;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) s += cnt[v];
+  // A block may be solved by two launches with different LDS footprints: this one takes the
+  // rows with nt_lo <= ceil(s/32) <= nt_max and leaves the others untouched.
+  const int nt = (s + 31) >> 5;
+  const bool fits = s <= kTlSmax;
+  if (fits ? (nt < a.nt_lo || nt > a.nt_max) : (32 * a.nt_max < kTlSmax)) return;
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch) {
+    const int col = tid + 256 * ch;
+    int before = 0;
+    for (int v = 0; v < 4 * ch + wave; ++v) before += cnt[v];
+    const int myrank = before + __popcll(bal[ch] & ((1ull << lane) - 1ull));
+    if (sel[ch] && fits) q[myrank] = col;
+    if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[ch] ? 1 : 0;
+  }
+  if (SEL == SEL_THRESHOLD) {
+    if (tid == 0) a.row_cnt[i] = s;  // summed at the start of the next block
+  }
+  float* lam_g = a.Lam + i * a.ldl;
+  if (s == 0 || !fits) {  // !fits cannot happen for a launch chosen by the host
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const int col = tid + 256 * ch;
+      if (col < a.bw) lam_g[col] = 0.f;
+    }
+    if (!fits && tid == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
+    return;
+  }
+  __syncthreads();
+  TL_MARK(0);
+  if (tid < 32 * nt) u[tid] = (tid < s) ? wrow[q[tid]] : 0.f;
+  __syncthreads();  // wrow and key are dead from here on
+
+  // ---- gather R_hat into the tiles: thread <-> (rows tid/32 + 8e, column tid%32) of a tile;
+  //      up to four tiles of a tile row are fetched together, all loads unconditional from
+  //      clamped (valid) indices and masked when stored ----
+  {
+    const float* G = a.P + a.j1 * a.b + a.j1;
+    const int tr = tid >> 5, tc = tid & 31;
+    for (int ti = 0; ti < nt; ++ti) {
+      const float* grow[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        grow[e] = G + (int64_t)q[min(32 * ti + tr + 8 * e, s - 1)] * a.b;
+      for (int tj0 = 0; tj0 <= ti; tj0 += 4) {
+        float v[4][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int tj = min(tj0 + t, ti);
+          const int qc = q[min(32 * tj + tc, s - 1)];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[t][e] = grow[e][qc];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int tj = tj0 + t;
+          if (tj <= ti) {
+            float* T = tl_tile(tiles, ti, tj);
+            const int cc = 32 * tj + tc;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int rr = 32 * ti + tr + 8 * e;
+              const float ident = (rr == cc) ? 1.f : 0.f;
+              T[(tr + 8 * e) * kTlLd + tc] = (rr < s && cc < s) ? v[t][e] : ident;
+            }
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  TL_MARK(1);
+  // ---- blocked Cholesky, forward substitution carried along ----
+  bool bad = false;
+  for (int p = 0; p < nt; ++p) {
+    float* Tp = tl_tile(tiles, p, p);
+    // the eliminating wavefront rotates, so that concurrent workgroups of a compute unit do not
+    // all run this latency-bound step on the same SIMD
+    if (wave == ((p + (int)blockIdx.x) & 3)) bad = tl_pivots(Tp, aux, lo, hi) || bad;
+    __syncthreads();
+    TL_MARK(2);
+    for (int ii = p + 1 + wave; ii < nt; ii += 4) {  // L_ip = A_ip T^T
+      float* Aip = tl_tile(tiles, ii, p);
+      f32x16 C;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) C[r] = 0.f;
+      tl_mma(C, Aip, Tp, 1.f, lo, hi);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Aip[tl_row(r, hi) * kTlLd + lo] = C[r];
+    }
+    if (wave == 3 && lane < 32) {  // y_p = T u_p (T is zero above its diagonal)
+      float acc = 0.f;
+#pragma unroll
+      for (int k = 0; k < 32; ++k) acc = fmaf(Tp[lane * kTlLd + k], u[32 * p + k], acc);
+      u[32 * p + lane] = acc;
+    }
+    __syncthreads();
+    TL_MARK(3);
+    {
+      int t = 0;
+      for (int ii = p + 1; ii < nt; ++ii)
+        for (int l = p + 1; l <= ii; ++l, ++t) {
+          if ((t & 3) != wave) continue;
+          float* Ail = tl_tile(tiles, ii, l);
+          f32x16 C;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) C[r] = Ail[tl_row(r, hi) * kTlLd + lo];
+          tl_mma(C, tl_tile(tiles, ii, p), tl_tile(tiles, l, p), -1.f, lo, hi);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) Ail[tl_row(r, hi) * kTlLd + lo] = C[r];
+        }
+      const int row = 32 * (p + 1) + tid;  // u_i -= L_ip y_p
+      if (row < 32 * nt) {
+        const float* Lr = tl_tile(tiles, row >> 5, p) + (row & 31) * kTlLd;
+        float acc = u[row];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) acc = fmaf(-Lr[k], u[32 * p + k], acc);
+        u[row] = acc;
+      }
+    }
+    __syncthreads();
+    TL_MARK(4);
+  }
+  if (bad && lane == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
+
+  // ---- L^T lambda = y, last tile row first ----
+  for (int p = nt - 1; p >= 0; --p) {
+    const float* Tp = tl_tile(tiles, p, p);
+    if (wave == 0 && lane < 32) {  // lambda_p = T^T y_p
+      float acc = 0.f;
+#pragma unroll
+      for (int k = 0; k < 32; ++k) acc = fmaf(Tp[k * kTlLd + lane], u[32 * p + k], acc);
+      lam[32 * p + lane] = acc;
+    }
+    __syncthreads();
+    if (tid < 32 * p) {  // y_j -= L_pj^T lambda_p for the tile rows above
+      const float* Lc = tl_tile(tiles, p, tid >> 5) + (tid & 31);
+      float acc = u[tid];
+#pragma unroll
+      for (int r = 0; r < 32; ++r) acc = fmaf(-Lc[r * kTlLd], lam[32 * p + r], acc);
+      u[tid] = acc;
+    }
+    __syncthreads();
+  }
+
+  TL_MARK(5);
+  // ---- lambda row: zeros except lambda_k at column q_k ----
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch) wrow[tid + 256 * ch] = 0.f;
+  __syncthreads();
+  if (tid < s) wrow[q[tid]] = lam[tid];
+  __syncthreads();
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch) {
+    const int col = tid + 256 * ch;
+    if (col < a.bw) lam_g[col] = wrow[col];
+  }
+  TL_MARK(6);
+#ifdef TL_DEBUG
+  if (tid == 0 && (blockIdx.x == 5 || blockIdx.x == 3000) && a.j1 == 1024)
+    printf("row %d s %d nt %d: select %lld gather %lld pivots %lld trsm %lld trailing %lld backsub %lld out %lld (x10ns)\n",
+           (int)blockIdx.x, s, nt, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
+#endif
+}
+
+// ------------------------------------------------------------------------------------------
 // W[:, j1:b] -= Lam * P[j1:j2, j1:b]; removed weights of the block become exact zeros.
 // W[:, col0:col_end] -= Lam[:, 0:K] * P[prow0:prow0+K, col0:col_end]; entries of the column
 // range [zj1, zj2) whose mask byte is set are written as exact zeros.
@@ -1127,19 +1471,36 @@ __global__ void k_init_state(SelState* st, long long r) {
 }
 
 template <int SEL>
-static void launch_solve(hipStream_t s, const SolveArgs& a, int smax) {
-  // columns per lane from the block width, rows per lane from the largest possible s
-  if (a.bw <= 64 || smax <= 64) {
+static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
+  if (a.bw <= 128 && smax <= 64) {
     constexpr int kWpb = 4;
     const size_t smem = kWpb * sizeof(SolveMfmaSmem);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfma<SEL, kWpb>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb>), dim3((unsigned)ceil_div(a.c, kWpb)),
                        dim3(64 * kWpb), smem, s, a);
-  } else if (a.bw <= 128) {
+  } else if (a.bw <= 128) {  // few tile rows: the register-resident kernel keeps more rows in flight
     hipLaunchKernelGGL((k_solve_wide<SEL, 128>), dim3((unsigned)a.c), dim3(128), 0, s, a);
   } else {
-    hipLaunchKernelGGL((k_solve_wide<SEL, 256>), dim3((unsigned)a.c), dim3(256), 0, s, a);
+    // LDS per row grows with the square of the tile rows; systems of up to 160 unknowns leave
+    // room for two workgroups per compute unit, so when s varies from row to row (and may be
+    // larger) the small rows get a launch of their own.
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_tiled<SEL>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)tl_smem_bytes(kTlSmax / 32));
+    const int nt_all = std::max(3, (std::min(smax, kTlSmax) + 31) / 32);
+    constexpr int kNtTwo = 5;
+    const bool split = SEL != SEL_NM && nt_all > kNtTwo;
+    a.nt_lo = 0;
+    a.nt_max = split ? kNtTwo : nt_all;
+    hipLaunchKernelGGL((k_solve_tiled<SEL>), dim3((unsigned)a.c), dim3(256),
+                       tl_smem_bytes(a.nt_max), s, a);
+    if (split) {
+      a.nt_lo = kNtTwo + 1;
+      a.nt_max = kTlSmax / 32;  // the launch that reports systems beyond the solver's limit
+      hipLaunchKernelGGL((k_solve_tiled<SEL>), dim3((unsigned)a.c), dim3(256),
+                         tl_smem_bytes(a.nt_max), s, a);
+    }
   }
 }
 
@@ -1254,6 +1615,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.ldl = ldl;
     sa.n = o->n;
     sa.m = o->m;
+    sa.nt_lo = sa.nt_max = 0;
     if (o->mask_in) {
       launch_solve<SEL_GIVEN>(s, sa, bw);
     } else if (o->mode == THANOS_NM) {

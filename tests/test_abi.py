@@ -54,6 +54,13 @@ def test_host_side_argument_checks(L):
     big = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=512,
                       damping=0.01)
     assert t.thanos_prune_workspace_bytes(64, 256, big) == 0          # B > 256 unsupported
+    # n:m: blocks of up to 512 columns as long as a row's system has at most 256 unknowns
+    nm512 = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=512, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 1024, nm512) > 0
+    nm34 = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=3, m=4, block_size=512, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 1024, nm34) == 0        # 384 unknowns per row
+    nm1k = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=1, m=4, block_size=1024, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 1024, nm1k) == 0
     assert t.thanos_factor_workspace_bytes(1000) >= 3 * 1024 * 1024 * 4
     p1 = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=1.0, n=0, m=0, block_size=128,
                      damping=0.01)

@@ -97,6 +97,9 @@ def test_cfg1_nm(n, m, rho):
     (40, 450, 200, "unstructured"),     # wide block, nothing aligned
     (9, 40, 128, "unstructured"),       # single narrow block
     (5, 16, 1, "unstructured"),         # B = 1
+    (70, 1216, 512, "nm"),              # block 512 (the paper's n:m setting): 256 unknowns per row,
+                                        # last block 192 wide
+    (48, 768, 256, "nm14"),             # 1:4 at block 256: 64 unknowns per row in a wide block
 ])
 def test_ragged_shapes(c, b, B, mode):
     from tests.gpu_util import gpu_prune
@@ -108,8 +111,9 @@ def test_ragged_shapes(c, b, B, mode):
         Wo, Mo = orc.prune_unstructured(W, H, 0.5, B, 0.01)
         assert int(Mg.sum()) == (c * b) // 2
     else:
-        Wg, Mg, info = gpu_prune(W, H32, mode=mode, n=2, m=4, B=B)
-        Wo, Mo = orc.prune_nm(W, H, 2, 4, B, 0.01)
+        n, m = (1, 4) if mode == "nm14" else (2, 4)
+        Wg, Mg, info = gpu_prune(W, H32, mode="nm", n=n, m=m, B=B)
+        Wo, Mo = orc.prune_nm(W, H, n, m, B, 0.01)
     assert info == 0
     _check(W, H32, Wg, Mg, Wo, Mo)
 
