@@ -922,14 +922,16 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
 
 // ------------------------------------------------------------------------------------------
 // Mask + per-row solve for systems of 65..256 unknowns (block width <= 512): one workgroup of
-// four wavefronts per row of W.  R_hat = G[q, q] is held in LDS as the lower triangle of a grid
+// four or eight wavefronts per row of W.  R_hat = G[q, q] is held in LDS as the lower triangle of a grid
 // of 32x32 tiles (padded with the identity past s) and factored by a right-looking blocked
 // Cholesky, R_hat = L L^T, 32 columns per step:
 //   1. one wavefront eliminates the diagonal tile with rank-1 MFMAs on its accumulator-layout
 //      copy (row k of a symmetric tile is both operands of D -= u u^T / d) and carries a second
 //      tile that starts as I along, which ends as T = L_pp^{-1}; T replaces the diagonal tile;
 //   2. the tiles below it become L_ip = A_ip T^T (one 32x32x32 product each), y_p = T u_p;
-//   3. the tiles right of the panel get A_il -= L_ip L_lp^T, the right-hand side u_i -= L_ip y_p.
+//   3. the tiles right of the panel get A_il -= L_ip L_lp^T, the right-hand side u_i -= L_ip y_p;
+//      meanwhile one wavefront updates the next diagonal tile and runs step 1 on it (look-ahead:
+//      the elimination is a chain of dependent instructions, the rest is throughput work).
 // L^T lambda = y is then solved from the last tile row upwards with the same T tiles.
 // All products are fp32 MFMAs (v_mfma_f32_32x32x2_f32) on operands read from LDS.
 constexpr int kTlLd = 33;          // LDS row stride of a tile (conflict-free rows and columns)
@@ -959,16 +961,13 @@ __device__ __forceinline__ void tl_mma(f32x16& acc, const float* pa, const float
   for (int e = 0; e < 16; ++e)
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(sign * av[e], bv[e], acc, 0, 0, 0);
 }
-// Eliminates the symmetric tile at Dt and overwrites it with T = L^{-1} (lower triangular, zeros
-// above the diagonal), L its Cholesky factor.  One wavefront.  Returns true if a pivot was not
-// positive.
-__device__ __forceinline__ bool tl_pivots(float* Dt, float* aux, int lo, int hi) {
-  f32x16 D, E;
+// Eliminates the symmetric tile D (accumulator layout) and writes T = L^{-1} (lower triangular,
+// zeros above the diagonal), L its Cholesky factor, to Dt.  One wavefront.  Returns true if a
+// pivot was not positive.
+__device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int lo, int hi) {
+  f32x16 E;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    D[r] = Dt[tl_row(r, hi) * kTlLd + lo];
-    E[r] = (tl_row(r, hi) == lo) ? 1.f : 0.f;
-  }
+  for (int r = 0; r < 16; ++r) E[r] = (tl_row(r, hi) == lo) ? 1.f : 0.f;
   const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
   float dl = 1.f;  // pivot of column lo
 #pragma unroll
@@ -995,8 +994,11 @@ __device__ __forceinline__ bool tl_pivots(float* Dt, float* aux, int lo, int hi)
   return bad;
 }
 
-template <int SEL>
-__global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
+template <int SEL, int NW>
+__global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(SolveArgs a) {
+  constexpr int NT = 64 * NW;       // threads
+  constexpr int CH = kTlBw / NT;    // block columns per thread
+  constexpr int RPT = 1024 / NT;    // tile elements per thread
   extern __shared__ __attribute__((aligned(16))) char solve_smem[];
   float* tiles = reinterpret_cast<float*>(solve_smem);
   float* xtra = tiles + tl_ntiles(a.nt_max) * kTlSz;
@@ -1004,7 +1006,7 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
   float* lam = xtra + kTlSmax;
   int* q = reinterpret_cast<int*>(xtra + 2 * kTlSmax);
   float* aux = xtra + 3 * kTlSmax;
-  int* cnt = reinterpret_cast<int*>(aux + 128);  // [2][4] selected, [2][4] ties
+  int* cnt = reinterpret_cast<int*>(aux + 128);  // per wavefront: selected, ties
   int* eqc = cnt + 8;
   // the block's weights and metric live in the tile area until the gather overwrites them, and
   // the lambda row is assembled there after the solve (nt_max >= 3: room for 2 * kTlBw floats)
@@ -1023,32 +1025,32 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
 #define TL_MARK(x) do {} while (0)
 #endif
 
-  // ---- selection of the block mask row M_i: column col = tid + 256 * ch ----
-  bool sel[2];
-  float wv[2];
+  // ---- selection of the block mask row M_i: column col = tid + NT * ch ----
+  bool sel[CH];
+  float wv[CH];
 #pragma unroll
-  for (int ch = 0; ch < 2; ++ch) {
-    const int col = tid + 256 * ch;
+  for (int ch = 0; ch < CH; ++ch) {
+    const int col = tid + NT * ch;
     wv[ch] = (col < a.bw) ? wrow_g[col] : 0.f;
     wrow[col] = wv[ch];
     sel[ch] = false;
   }
   if (SEL == SEL_GIVEN) {
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
-      const int col = tid + 256 * ch;
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
       sel[ch] = (col < a.bw) && a.mask_in[i * a.b + a.j1 + col] != 0;
     }
   } else if (SEL == SEL_NM) {
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
-      const int col = tid + 256 * ch;
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
       key[col] = (col < a.bw) ? fabsf(wv[ch]) * a.sx[a.j1 + col] : 0.f;
     }
     __syncthreads();
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
-      const int col = tid + 256 * ch;
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
       if (col < a.bw) {
         const int g0 = (col / a.m) * a.m;
         const float mine = key[col];
@@ -1060,39 +1062,42 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
         sel[ch] = rank < a.n;
       }
     }
-    if (a.row_skip && a.row_skip[i]) sel[0] = sel[1] = false;
+    if (a.row_skip && a.row_skip[i]) {
+#pragma unroll
+      for (int ch = 0; ch < CH; ++ch) sel[ch] = false;
+    }
   } else {  // SEL_THRESHOLD: key < tau, or key == tau and among the first need_eq ties
     const bool none = a.st->none != 0;
     const unsigned int tau = a.st->tau;
     const long long need_eq = a.st->need_eq;
-    bool lt[2], eq[2];
-    unsigned long long eqb[2];
+    bool lt[CH], eq[CH];
+    unsigned long long eqb[CH];
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
-      const int col = tid + 256 * ch;
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
       const bool in = (col < a.bw) && !none;
       const unsigned int kk = in ? metric_key(wv[ch], a.sx[a.j1 + col]) : 0xffffffffu;
       lt[ch] = in && kk < tau;
       eq[ch] = in && kk == tau;
       eqb[ch] = __ballot(eq[ch]);
-      if (lane == 0) eqc[4 * ch + wave] = __popcll(eqb[ch]);
+      if (lane == 0) eqc[NW * ch + wave] = __popcll(eqb[ch]);
     }
     __syncthreads();
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
+    for (int ch = 0; ch < CH; ++ch) {
       long long my = a.row_eq[i];
-      for (int v = 0; v < 4 * ch + wave; ++v) my += eqc[v];
+      for (int v = 0; v < NW * ch + wave; ++v) my += eqc[v];
       my += __popcll(eqb[ch] & ((1ull << lane) - 1ull));
       sel[ch] = lt[ch] || (eq[ch] && my < need_eq);
     }
   }
 
   // ---- q = phi(M_i) (ascending column indices) and s ----
-  unsigned long long bal[2];
+  unsigned long long bal[CH];
 #pragma unroll
-  for (int ch = 0; ch < 2; ++ch) {
+  for (int ch = 0; ch < CH; ++ch) {
     bal[ch] = __ballot(sel[ch]);
-    if (lane == 0) cnt[4 * ch + wave] = __popcll(bal[ch]);
+    if (lane == 0) cnt[NW * ch + wave] = __popcll(bal[ch]);
   }
   __syncthreads();
   int s = 0;
@@ -1104,12 +1109,11 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
   const bool fits = s <= kTlSmax;
   if (fits ? (nt < a.nt_lo || nt > a.nt_max) : (32 * a.nt_max < kTlSmax)) return;
 #pragma unroll
-  for (int ch = 0; ch < 2; ++ch) {
-    const int col = tid + 256 * ch;
+  for (int ch = 0; ch < CH; ++ch) {
+    const int col = tid + NT * ch;
     int before = 0;
-    for (int v = 0; v < 4 * ch + wave; ++v) before += cnt[v];
-    const int myrank = before + __popcll(bal[ch] & ((1ull << lane) - 1ull));
-    if (sel[ch] && fits) q[myrank] = col;
+    for (int v = 0; v < NW * ch + wave; ++v) before += cnt[v];
+    if (sel[ch] && fits) q[before + __popcll(bal[ch] & ((1ull << lane) - 1ull))] = col;
     if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[ch] ? 1 : 0;
   }
   if (SEL == SEL_THRESHOLD) {
@@ -1118,8 +1122,8 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
   float* lam_g = a.Lam + i * a.ldl;
   if (s == 0 || !fits) {  // !fits cannot happen for a launch chosen by the host
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
-      const int col = tid + 256 * ch;
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
       if (col < a.bw) lam_g[col] = 0.f;
     }
     if (!fits && tid == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
@@ -1130,25 +1134,25 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
   if (tid < 32 * nt) u[tid] = (tid < s) ? wrow[q[tid]] : 0.f;
   __syncthreads();  // wrow and key are dead from here on
 
-  // ---- gather R_hat into the tiles: thread <-> (rows tid/32 + 8e, column tid%32) of a tile;
+  // ---- gather R_hat into the tiles: thread <-> (rows tid/32 + (NT/32)e, column tid%32) of a tile;
   //      up to four tiles of a tile row are fetched together, all loads unconditional from
   //      clamped (valid) indices and masked when stored ----
   {
     const float* G = a.P + a.j1 * a.b + a.j1;
     const int tr = tid >> 5, tc = tid & 31;
     for (int ti = 0; ti < nt; ++ti) {
-      const float* grow[4];
+      const float* grow[RPT];
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        grow[e] = G + (int64_t)q[min(32 * ti + tr + 8 * e, s - 1)] * a.b;
+      for (int e = 0; e < RPT; ++e)
+        grow[e] = G + (int64_t)q[min(32 * ti + tr + (NT / 32) * e, s - 1)] * a.b;
       for (int tj0 = 0; tj0 <= ti; tj0 += 4) {
-        float v[4][4];
+        float v[4][RPT];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int tj = min(tj0 + t, ti);
           const int qc = q[min(32 * tj + tc, s - 1)];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[t][e] = grow[e][qc];
+          for (int e = 0; e < RPT; ++e) v[t][e] = grow[e][qc];
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -1157,10 +1161,10 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
             float* T = tl_tile(tiles, ti, tj);
             const int cc = 32 * tj + tc;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int rr = 32 * ti + tr + 8 * e;
+            for (int e = 0; e < RPT; ++e) {
+              const int rr = 32 * ti + tr + (NT / 32) * e;
               const float ident = (rr == cc) ? 1.f : 0.f;
-              T[(tr + 8 * e) * kTlLd + tc] = (rr < s && cc < s) ? v[t][e] : ident;
+              T[(tr + (NT / 32) * e) * kTlLd + tc] = (rr < s && cc < s) ? v[t][e] : ident;
             }
           }
         }
@@ -1168,49 +1172,79 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
     }
   }
   __syncthreads();
-
   TL_MARK(1);
-  // ---- blocked Cholesky, forward substitution carried along ----
+
+  // ---- blocked Cholesky with look-ahead, forward substitution carried along.  The wavefront
+  //      that eliminates a diagonal tile rotates, so that concurrent workgroups of a compute
+  //      unit do not run this latency-bound step on the same SIMD. ----
   bool bad = false;
+  if (wave == ((int)blockIdx.x & (NW - 1))) {
+    f32x16 D;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) D[r] = tiles[tl_row(r, hi) * kTlLd + lo];
+    bad = tl_pivots(D, tiles, aux, lo, hi);
+  }
+  __syncthreads();
+  TL_MARK(2);
   for (int p = 0; p < nt; ++p) {
     float* Tp = tl_tile(tiles, p, p);
-    // the eliminating wavefront rotates, so that concurrent workgroups of a compute unit do not
-    // all run this latency-bound step on the same SIMD
-    if (wave == ((p + (int)blockIdx.x) & 3)) bad = tl_pivots(Tp, aux, lo, hi) || bad;
-    __syncthreads();
-    TL_MARK(2);
-    for (int ii = p + 1 + wave; ii < nt; ii += 4) {  // L_ip = A_ip T^T
-      float* Aip = tl_tile(tiles, ii, p);
-      f32x16 C;
+    {  // panel: L_ip = A_ip T^T
+      for (int ii = p + 1 + wave; ii < nt; ii += NW) {
+        float* Aip = tl_tile(tiles, ii, p);
+        f32x16 C;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) C[r] = 0.f;
-      tl_mma(C, Aip, Tp, 1.f, lo, hi);
+        for (int r = 0; r < 16; ++r) C[r] = 0.f;
+        tl_mma(C, Aip, Tp, 1.f, lo, hi);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) Aip[tl_row(r, hi) * kTlLd + lo] = C[r];
-    }
-    if (wave == 3 && lane < 32) {  // y_p = T u_p (T is zero above its diagonal)
-      float acc = 0.f;
+        for (int r = 0; r < 16; ++r) Aip[tl_row(r, hi) * kTlLd + lo] = C[r];
+      }
+      if (wave == NW - 1 && lane < 32) {  // y_p = T u_p (T is zero above its diagonal)
+        float acc = 0.f;
 #pragma unroll
-      for (int k = 0; k < 32; ++k) acc = fmaf(Tp[lane * kTlLd + k], u[32 * p + k], acc);
-      u[32 * p + lane] = acc;
+        for (int k = 0; k < 32; ++k) acc = fmaf(Tp[lane * kTlLd + k], u[32 * p + k], acc);
+        u[32 * p + lane] = acc;
+      }
     }
     __syncthreads();
     TL_MARK(3);
-    {
-      int t = 0;
-      for (int ii = p + 1; ii < nt; ++ii)
-        for (int l = p + 1; l <= ii; ++l, ++t) {
-          if ((t & 3) != wave) continue;
-          float* Ail = tl_tile(tiles, ii, l);
-          f32x16 C;
+    if (p + 1 == nt) break;
+    // One wavefront brings the next diagonal tile up to date and eliminates it at once (the
+    // tile stays in registers); the others apply panel p to the rest of the trailing
+    // matrix, the tiles of column p+1 first, and to the right-hand side.
+    const int pw = (p + 1 + (int)blockIdx.x) & (NW - 1);
+    if (wave == pw) {
+      float* Dn = tl_tile(tiles, p + 1, p + 1);
+      const float* Lp = tl_tile(tiles, p + 1, p);
+      f32x16 D;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) C[r] = Ail[tl_row(r, hi) * kTlLd + lo];
-          tl_mma(C, tl_tile(tiles, ii, p), tl_tile(tiles, l, p), -1.f, lo, hi);
+      for (int r = 0; r < 16; ++r) D[r] = Dn[tl_row(r, hi) * kTlLd + lo];
+      tl_mma(D, Lp, Lp, -1.f, lo, hi);
+      bad = tl_pivots(D, Dn, aux, lo, hi) || bad;
+    } else {
+      const int widx = wave - (wave > pw ? 1 : 0);  // 0..NW-2
+      int t = 0, mine = widx;
+      auto upd = [&](int ii, int l) {
+        float* Ail = tl_tile(tiles, ii, l);
+        f32x16 C;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) Ail[tl_row(r, hi) * kTlLd + lo] = C[r];
+        for (int r = 0; r < 16; ++r) C[r] = Ail[tl_row(r, hi) * kTlLd + lo];
+        tl_mma(C, tl_tile(tiles, ii, p), tl_tile(tiles, l, p), -1.f, lo, hi);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Ail[tl_row(r, hi) * kTlLd + lo] = C[r];
+      };
+      for (int ii = p + 2; ii < nt; ++ii, ++t)
+        if (t == mine) {
+          upd(ii, p + 1);
+          mine += NW - 1;
         }
-      const int row = 32 * (p + 1) + tid;  // u_i -= L_ip y_p
-      if (row < 32 * nt) {
+      for (int l = p + 2; l < nt; ++l)
+        for (int ii = l; ii < nt; ++ii, ++t)
+          if (t == mine) {
+            upd(ii, l);
+            mine += NW - 1;
+          }
+      for (int row = 32 * (p + 1) + 64 * widx + lane; row < 32 * nt; row += 64 * (NW - 1)) {
+        // u_i -= L_ip y_p
         const float* Lr = tl_tile(tiles, row >> 5, p) + (row & 31) * kTlLd;
         float acc = u[row];
 #pragma unroll
@@ -1233,7 +1267,7 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
       lam[32 * p + lane] = acc;
     }
     __syncthreads();
-    if (tid < 32 * p) {  // y_j -= L_pj^T lambda_p for the tile rows above
+    if (tid < 32 * p) {  // y_j -= L_pj^T lambda_p for the tile rows above (32 p <= 224 < NT)
       const float* Lc = tl_tile(tiles, p, tid >> 5) + (tid & 31);
       float acc = u[tid];
 #pragma unroll
@@ -1242,23 +1276,23 @@ __global__ __launch_bounds__(256, 2) void k_solve_tiled(SolveArgs a) {
     }
     __syncthreads();
   }
-
   TL_MARK(5);
+
   // ---- lambda row: zeros except lambda_k at column q_k ----
 #pragma unroll
-  for (int ch = 0; ch < 2; ++ch) wrow[tid + 256 * ch] = 0.f;
+  for (int ch = 0; ch < CH; ++ch) wrow[tid + NT * ch] = 0.f;
   __syncthreads();
   if (tid < s) wrow[q[tid]] = lam[tid];
   __syncthreads();
 #pragma unroll
-  for (int ch = 0; ch < 2; ++ch) {
-    const int col = tid + 256 * ch;
+  for (int ch = 0; ch < CH; ++ch) {
+    const int col = tid + NT * ch;
     if (col < a.bw) lam_g[col] = wrow[col];
   }
   TL_MARK(6);
 #ifdef TL_DEBUG
   if (tid == 0 && (blockIdx.x == 5 || blockIdx.x == 3000) && a.j1 == 1024)
-    printf("row %d s %d nt %d: select %lld gather %lld pivots %lld trsm %lld trailing %lld backsub %lld out %lld (x10ns)\n",
+    printf("row %d s %d nt %d: select %lld gather %lld pivot0 %lld panel %lld lookahead %lld backsub %lld out %lld (x10ns)\n",
            (int)blockIdx.x, s, nt, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
 #endif
 }
@@ -1485,20 +1519,28 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
     // LDS per row grows with the square of the tile rows; systems of up to 160 unknowns leave
     // room for two workgroups per compute unit, so when s varies from row to row (and may be
     // larger) the small rows get a launch of their own.
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_tiled<SEL>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)tl_smem_bytes(kTlSmax / 32));
     const int nt_all = std::max(3, (std::min(smax, kTlSmax) + 31) / 32);
     constexpr int kNtTwo = 5;
     const bool split = SEL != SEL_NM && nt_all > kNtTwo;
     a.nt_lo = 0;
     a.nt_max = split ? kNtTwo : nt_all;
-    hipLaunchKernelGGL((k_solve_tiled<SEL>), dim3((unsigned)a.c), dim3(256),
+    if (a.nt_max <= 4) {  // small footprint: three workgroups of four wavefronts per compute unit
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_tiled<SEL, 4>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)tl_smem_bytes(4));
+      hipLaunchKernelGGL((k_solve_tiled<SEL, 4>), dim3((unsigned)a.c), dim3(256),
+                         tl_smem_bytes(a.nt_max), s, a);
+      return;
+    }
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_tiled<SEL, 8>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)tl_smem_bytes(kTlSmax / 32));
+    hipLaunchKernelGGL((k_solve_tiled<SEL, 8>), dim3((unsigned)a.c), dim3(512),
                        tl_smem_bytes(a.nt_max), s, a);
     if (split) {
       a.nt_lo = kNtTwo + 1;
       a.nt_max = kTlSmax / 32;  // the launch that reports systems beyond the solver's limit
-      hipLaunchKernelGGL((k_solve_tiled<SEL>), dim3((unsigned)a.c), dim3(256),
+      hipLaunchKernelGGL((k_solve_tiled<SEL, 8>), dim3((unsigned)a.c), dim3(512),
                          tl_smem_bytes(a.nt_max), s, a);
     }
   }
