@@ -57,8 +57,10 @@ typedef struct {
                          means 6/10.  Ignored for THANOS_NM.                                  */
   int32_t n, m;       /* THANOS_NM: n of every m consecutive weights of a row are removed;
                          0 < n < m <= 16, m divides block_size and b                          */
-  int32_t block_size; /* B: columns pruned per sweep step, 1 <= B <= 256; last block may be
-                         narrower (unstructured only)                                         */
+  int32_t block_size; /* B: columns pruned per sweep step, B >= 1.  A row's system of one block
+                         must not exceed 256 unknowns: B <= 256 in general; THANOS_NM without
+                         mask_in also takes B <= 512 with B*n/m <= 256 (2:4 and 4:8 at the
+                         B = 512 of the paper's experiments).  The last block may be narrower. */
   float damping;      /* H_d = H + damping * mean(diag H) * I (relative damping, >= 0)        */
   const uint8_t* mask_in;  /* optional c*b device mask that replaces the selection step
                               (1 = remove); NULL = select as the paper does                   */
@@ -129,7 +131,8 @@ size_t thanos_factor_workspace_bytes(int64_t b);
  * then meaningless; other rows are unaffected).
  * Ties in the metric are broken by ascending (row, column).
  * Errors: INVALID_ARG (NULL, sizes, n/m/B constraints, p or alpha outside [0,1), alpha > 0
- * without H), UNSUPPORTED (block_size > 256, m > 16, alpha > 0 with THANOS_UNSTRUCTURED),
+ * without H), UNSUPPORTED (block_size beyond the limits above, m > 16, alpha > 0 with
+ * THANOS_UNSTRUCTURED),
  * WORKSPACE, HIP.
  */
 thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,

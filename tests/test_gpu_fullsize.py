@@ -35,11 +35,11 @@ def layer():
     return types.SimpleNamespace(W=W, X=X, H=H)
 
 
-def _prune(layer, mode, **kw):
+def _prune(layer, mode, block=BLOCK):
     import torch
     import paper_2504_05346_amd as th
     o = th.PruneOpts(mode=th.THANOS_NM if mode == "nm" else th.THANOS_UNSTRUCTURED,
-                     sparsity=0.5, n=2, m=4, block_size=BLOCK, damping=DAMP)
+                     sparsity=0.5, n=2, m=4, block_size=block, damping=DAMP)
     ws = torch.empty((th.thanos_prune_workspace_bytes(C, B_IN, o),), dtype=torch.uint8,
                      device="cuda")
     Wo = torch.empty((C, B_IN), dtype=torch.float32, device="cuda")
@@ -99,8 +99,10 @@ def test_factor_properties_and_oracle(layer, host):
     assert np.linalg.norm(Ug - host.U) <= 5e-4 * np.linalg.norm(host.U)
 
 
-def test_nm_sweep_full_layer(layer, host):
-    Wo, M = _prune(layer, "nm")
+@pytest.mark.parametrize("block", [BLOCK, 512])   # 512: the paper's n:m setting (Experiments, "Models and evaluation"): 256
+def test_nm_sweep_full_layer(layer, host, block):  # unknowns per row and block
+    print(f"full-size 2:4 sweep, B={block}", flush=True)
+    Wo, M = _prune(layer, "nm", block)
     import torch
     grp = M.view(C, B_IN // 4, 4).sum(dim=2)
     assert bool((grp == 2).all())
@@ -110,14 +112,14 @@ def test_nm_sweep_full_layer(layer, host):
     Wg = Wo[rows].cpu().numpy().astype(np.float64)
     Mg = M[rows].cpu().numpy()
     Wref, Mref, mg = None, None, None
-    Wref, Mref = orc.prune_fast(W, host.H, mode="nm", n=2, m=4, B=BLOCK, damp=DAMP, U=host.U)
+    Wref, Mref = orc.prune_fast(W, host.H, mode="nm", n=2, m=4, B=block, damp=DAMP, U=host.U)
     same = np.all(Mg == Mref, axis=1)
     assert (Mg != Mref).mean() < 1e-4
     assert same.sum() >= len(rows) - 2
     for k in np.flatnonzero(same):
         assert np.linalg.norm(Wg[k] - Wref[k]) <= 1e-3 * np.linalg.norm(Wref[k])
     # rows whose mask differs somewhere: compare under the GPU's own mask
-    Wt, _ = orc.prune_fast(W, host.H, mode="nm", n=2, m=4, B=BLOCK, damp=DAMP, U=host.U, mask_in=Mg)
+    Wt, _ = orc.prune_fast(W, host.H, mode="nm", n=2, m=4, B=block, damp=DAMP, U=host.U, mask_in=Mg)
     assert np.linalg.norm(Wg - Wt) <= 1e-3 * np.linalg.norm(Wt)
 
 

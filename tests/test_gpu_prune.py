@@ -97,7 +97,7 @@ def test_cfg1_nm(n, m, rho):
     (40, 450, 200, "unstructured"),     # wide block, nothing aligned
     (9, 40, 128, "unstructured"),       # single narrow block
     (5, 16, 1, "unstructured"),         # B = 1
-    (70, 1216, 512, "nm"),              # block 512 (the paper's n:m setting): 256 unknowns per row,
+    (70, 1216, 512, "nm"),              # block 512 (the n:m setting of the Experiments section): 256 unknowns per row,
                                         # last block 192 wide
     (48, 768, 256, "nm14"),             # 1:4 at block 256: 64 unknowns per row in a wide block
 ])
@@ -352,3 +352,27 @@ def test_medium_layer_teacher_forced(mode):
     eo = orc.reconstruction_error(W, Wo, H)
     eg = orc.reconstruction_error(W, Wg.astype(np.float64), H)
     assert abs(eg - eo) <= 0.01 * eo
+
+
+@pytest.mark.parametrize("B", [64, 128, 256])
+def test_singular_row_system_is_reported(B):
+    # A factor with a zero column makes G = U_kk^T U_kk singular in that column: the one row
+    # whose mask contains it must be reported as -(row + 1); the three block sizes reach the
+    # three per-row solvers (register tiles, 128 threads, LDS tiles).
+    from tests.gpu_util import gpu_prune, gpu_factor
+    c, b, bad_row, bad_col = 12, 2 * B, 3, 5
+    W, H32 = _layer(c, b, 4 * b, "f32", seed=B)
+    U, xn2, info = gpu_factor(H32, 0.01)
+    assert info == 0
+    U[:, bad_col] = 0.0
+    rng = np.random.default_rng(B)
+    M = (rng.random((c, b)) < 0.6).astype(np.uint8)
+    M[:, bad_col] = 0
+    M[bad_row, bad_col] = 1
+    print(f"singular system B={B}", flush=True)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=B, mask_in=M, U=U, xnorm2=xn2)
+    assert info == -(bad_row + 1)
+    np.testing.assert_array_equal(Mg, M)
+    ok = np.arange(c) != bad_row
+    assert np.all(np.isfinite(Wg[ok]))
+    assert np.all(Wg[ok][M[ok] == 1] == 0.0)
