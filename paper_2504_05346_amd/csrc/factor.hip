@@ -222,14 +222,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
   const int lo = lane & 31, hi = lane >> 5;
   float* A = Ap + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
   float* Li = Linv + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
-#ifdef CD_DEBUG
-  long long tc[16], tr[16];
-  int nt = 0;
-#define CD_MARK() do { tc[nt] = clock64(); tr[nt] = wall_clock64(); ++nt; } while (0)
-#else
-#define CD_MARK() do {} while (0)
-#endif
-  CD_MARK();
 
   // lower triangle -> S, mirrored inside the diagonal 32x32 tiles (the pivot loop wants them
   // symmetric); the strict upper 32-tiles stay undefined (scratch).  The first 32 columns are
@@ -268,7 +260,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
     put(e / 8, (e % 8) * 4, va[q]);
   }
   __syncthreads();
-  CD_MARK();
 
   int badk = -1;
   for (int j = 0; j < NB / 32; ++j) {
@@ -290,7 +281,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
       }
     }
     __syncthreads();
-    CD_MARK();
     // trailing tiles (i, l), j < l <= i < 4, dealt round-robin to the wavefronts
     {
       int t = 0;
@@ -306,7 +296,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
         }
     }
     __syncthreads();
-    CD_MARK();
   }
   if (badk >= 0 && tid == 0) {
     const int64_t orig = b - ((int64_t)kb_glob * NB + badk);  // 1-based original column
@@ -328,7 +317,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
     cd_tile_store(T + p1 * kCdLd + p0, C, -1.f, lo, hi);
   }
   __syncthreads();
-  CD_MARK();
   // 64 -> 128: W = L[64:128, 0:64] T[0:64, 0:64] into S[0:64, 64:128], then
   // T[64:128, 0:64] = -T[64:128, 64:128] W; one 32x32 tile per wavefront.
   {
@@ -351,7 +339,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
     cd_tile_store(T + (64 + 32 * ti) * kCdLd + 32 * tj, C, -1.f, lo, hi);
   }
   __syncthreads();
-  CD_MARK();
   {
     constexpr int kVec = NB * (NB / 4) / 256;
     float4 l[kVec], t[kVec];
@@ -382,15 +369,6 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
       *reinterpret_cast<float4*>(Li + (int64_t)i * bp + c4) = t[q];
     }
   }
-#ifdef CD_DEBUG
-  __syncthreads();
-  CD_MARK();
-  if (tid == 0)
-    for (int q = 1; q < nt; ++q) {
-      Li[2 * q] = (float)(tc[q] - tc[q - 1]);
-      Li[2 * q + 1] = (float)(tr[q] - tr[q - 1]);
-    }
-#endif
 }
 
 // ------------------------------------------------------------------------------------------

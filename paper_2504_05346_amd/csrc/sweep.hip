@@ -1017,13 +1017,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
   const int lo = lane & 31, hi = lane >> 5;
   const int64_t i = blockIdx.x;
   const float* wrow_g = a.W + i * a.b + a.j1;
-#ifdef TL_DEBUG
-  long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  long long tlast = wall_clock64();
-#define TL_MARK(x) do { const long long t_ = wall_clock64(); tph[x] += t_ - tlast; tlast = t_; } while (0)
-#else
-#define TL_MARK(x) do {} while (0)
-#endif
 
   // ---- selection of the block mask row M_i: column col = tid + NT * ch ----
   bool sel[CH];
@@ -1130,7 +1123,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
     return;
   }
   __syncthreads();
-  TL_MARK(0);
   if (tid < 32 * nt) u[tid] = (tid < s) ? wrow[q[tid]] : 0.f;
   __syncthreads();  // wrow and key are dead from here on
 
@@ -1172,7 +1164,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
     }
   }
   __syncthreads();
-  TL_MARK(1);
 
   // ---- blocked Cholesky with look-ahead, forward substitution carried along.  The wavefront
   //      that eliminates a diagonal tile rotates, so that concurrent workgroups of a compute
@@ -1185,7 +1176,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
     bad = tl_pivots(D, tiles, aux, lo, hi);
   }
   __syncthreads();
-  TL_MARK(2);
   for (int p = 0; p < nt; ++p) {
     float* Tp = tl_tile(tiles, p, p);
     {  // panel: L_ip = A_ip T^T
@@ -1206,7 +1196,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
       }
     }
     __syncthreads();
-    TL_MARK(3);
     if (p + 1 == nt) break;
     // One wavefront brings the next diagonal tile up to date and eliminates it at once (the
     // tile stays in registers); the others apply panel p to the rest of the trailing
@@ -1253,7 +1242,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
       }
     }
     __syncthreads();
-    TL_MARK(4);
   }
   if (bad && lane == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
 
@@ -1276,7 +1264,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
     }
     __syncthreads();
   }
-  TL_MARK(5);
 
   // ---- lambda row: zeros except lambda_k at column q_k ----
 #pragma unroll
@@ -1289,12 +1276,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
     const int col = tid + NT * ch;
     if (col < a.bw) lam_g[col] = wrow[col];
   }
-  TL_MARK(6);
-#ifdef TL_DEBUG
-  if (tid == 0 && (blockIdx.x == 5 || blockIdx.x == 3000) && a.j1 == 1024)
-    printf("row %d s %d nt %d: select %lld gather %lld pivot0 %lld panel %lld lookahead %lld backsub %lld out %lld (x10ns)\n",
-           (int)blockIdx.x, s, nt, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
-#endif
 }
 
 // ------------------------------------------------------------------------------------------
