@@ -12,7 +12,7 @@ struct GemmArgs {
   int M, N, K;
   float alpha, beta;
   int lower_only;
-  int vec_a, vec_b;
+  int vec_a, vec_b, vec_c;
 };
 
 template <bool AK, bool BK>
@@ -27,32 +27,37 @@ __global__ __launch_bounds__(kXThreads) void k_gemm_f32(GemmArgs g) {
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, 0, g.K, g.vec_a, g.vec_b);
-  if (threadIdx.x >= 256) return;  // producer wavefronts hold no result
+  const float* T = x3_stage_tile(acc, sm);
+  // row pass: wavefront w takes rows w, w + 8, ..., lane l the columns 2l, 2l + 1
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  // Per 32x32 MFMA tile: 16 loads, then 16 stores.  A load placed right behind a store to the
-  // same array would have to wait for it, which serialises 64 memory round trips per thread.
+  const int c0 = 2 * lane;
+  float* Cg = g.C + (int64_t)m0 * g.ldc + n0 + c0;
+  if (m_ext == kTM && n_ext == kTN && g.vec_c) {  // whole tile, 8-byte aligned pairs
+    float2 old[16];
 #pragma unroll
-  for (int f = 0; f < 2; ++f)
+    for (int i = 0; i < 16; ++i)
+      old[i] = g.beta != 0.f ? *reinterpret_cast<const float2*>(Cg + (int64_t)(wave + 8 * i) * g.ldc)
+                             : make_float2(0.f, 0.f);
 #pragma unroll
-    for (int gg = 0; gg < 2; ++gg) {
-      const int col = acc_col(wn, gg, lane);
-      float old[16];
+    for (int i = 0; i < 16; ++i) {
+      const float2 t = *reinterpret_cast<const float2*>(T + (wave + 8 * i) * kXCLd + c0);
+      *reinterpret_cast<float2*>(Cg + (int64_t)(wave + 8 * i) * g.ldc) =
+          make_float2(g.beta * old[i].x + g.alpha * t.x, g.beta * old[i].y + g.alpha * t.y);
+    }
+  } else {
+    for (int i = 0; i < 16; ++i) {
+      const int row = wave + 8 * i;
+      if (row >= m_ext) break;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = acc_row(wm, f, r, lane);
-        old[r] = (g.beta != 0.f && row < m_ext && col < n_ext)
-                     ? g.C[(int64_t)(m0 + row) * g.ldc + (n0 + col)]
-                     : 0.f;
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = acc_row(wm, f, r, lane);
-        if (row < m_ext && col < n_ext)
-          g.C[(int64_t)(m0 + row) * g.ldc + (n0 + col)] =
-              g.beta * old[r] + g.alpha * acc.v[f][gg][r];
+      for (int e = 0; e < 2; ++e) {
+        if (c0 + e < n_ext) {
+          float* p = Cg + (int64_t)row * g.ldc + e;
+          const float o = g.beta != 0.f ? *p : 0.f;
+          *p = g.beta * o + g.alpha * T[row * kXCLd + c0 + e];
+        }
       }
     }
+  }
 }
 
 static inline bool vec_ok(const float* p, int64_t ld) {
@@ -64,7 +69,8 @@ thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, i
                        int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only) {
   if (M <= 0 || N <= 0) return THANOS_OK;
   GemmArgs g{A, B, C, lda, ldb, ldc, (int)M, (int)N, (int)K, alpha, beta, lower_only ? 1 : 0,
-             vec_ok(A, lda) ? 1 : 0, vec_ok(B, ldb) ? 1 : 0};
+             vec_ok(A, lda) ? 1 : 0, vec_ok(B, ldb) ? 1 : 0,
+             (reinterpret_cast<uintptr_t>(C) % 8 == 0 && ldc % 2 == 0) ? 1 : 0};
   dim3 grid((unsigned)ceil_div(N, kTN), (unsigned)ceil_div(M, kTM));
   void (*kern)(GemmArgs);
   if (!a_kmajor && !b_kmajor) kern = k_gemm_f32<false, false>;

@@ -284,4 +284,33 @@ __device__ __forceinline__ void gemm_tile_x3(TileAcc& acc, char* smem, const flo
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Write-out through LDS.  In the accumulator layout a store instruction of a wavefront covers
+// two 128-byte pieces of two different rows of C, and only the four multiplying wavefronts hold
+// data: 64 loads and 64 stores per thread for a read-modify-write, to rows that lie a whole row
+// of the big matrix apart.  Staged in LDS as plain fp32 rows (free once the product is done), the
+// tile is walked row by row by all eight wavefronts: a wavefront handles a full 512-byte row per
+// instruction, 16 rows each.
+constexpr int kXCLd = 136;  // floats per staged row (544 bytes: the two halves of a wavefront, four
+                            // rows apart, then write to disjoint banks)
+static_assert((size_t)kTM * kXCLd * sizeof(float) <= kXSmemBytes, "staged tile fits the LDS");
+
+// Called by all 512 threads right after gemm_tile_x3 (whose last barrier made the LDS free).
+__device__ __forceinline__ const float* x3_stage_tile(const TileAcc& acc, char* smem) {
+  float* C = reinterpret_cast<float*>(smem);
+  if (threadIdx.x < 256) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int col = acc_col(wn, g, lane);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) C[acc_row(wm, f, r, lane) * kXCLd + col] = acc.v[f][g][r];
+      }
+  }
+  __syncthreads();
+  return C;
+}
+
 }  // namespace thanos

@@ -1292,6 +1292,7 @@ struct UpdateArgs {
   int64_t col0, col_end;
   int64_t zj1, zj2;
   int K, ldl, vec_a, vec_b;
+  int vec_w;            // W 8-byte and mask 2-byte aligned, b and col0 even: row pass in pairs
 };
 
 __global__ __launch_bounds__(kXThreads) void k_update(UpdateArgs a) {
@@ -1305,36 +1306,48 @@ __global__ __launch_bounds__(kXThreads) void k_update(UpdateArgs a) {
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
-  if (threadIdx.x >= 256) return;  // producer wavefronts hold no result
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
-  const int64_t j2 = a.zj2;
-  const bool in_block = n0 < j2 && n0 + kTN > a.zj1;  // tile overlaps the columns holding masks
-  // per 32x32 MFMA tile: 16 loads, then 16 stores (see k_gemm_f32)
+  const float* T = x3_stage_tile(acc, sm);
+  // row pass: wavefront w takes rows w, w + 8, ..., lane l the columns 2l, 2l + 1
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = 2 * lane;
+  const int64_t cg = n0 + c0;
+  const bool in_block = n0 < a.zj2 && n0 + kTN > a.zj1;  // tile overlaps the columns holding masks
+  float* Wg = a.W + m0 * a.b + cg;
+  const uint8_t* Mg = a.mask + m0 * a.b + cg;
+  if (m_ext == kTM && n_ext == kTN && a.vec_w) {  // whole tile, aligned pairs
+    const bool z0 = in_block && cg >= a.zj1 && cg < a.zj2;
+    const bool z1 = in_block && cg + 1 >= a.zj1 && cg + 1 < a.zj2;
+    float2 old[16];
+    unsigned short mk[16];
 #pragma unroll
-  for (int f = 0; f < 2; ++f)
+    for (int i = 0; i < 16; ++i) {
+      const int64_t off = (int64_t)(wave + 8 * i) * a.b;
+      old[i] = *reinterpret_cast<const float2*>(Wg + off);
+      mk[i] = in_block ? *reinterpret_cast<const unsigned short*>(Mg + off) : (unsigned short)0;
+    }
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      const int col = acc_col(wn, g, lane);
-      const int64_t cg = n0 + col;
-      float old[16];
-      bool mk[16];
+    for (int i = 0; i < 16; ++i) {
+      const int row = wave + 8 * i;
+      const float2 t = *reinterpret_cast<const float2*>(T + row * kXCLd + c0);
+      float2 o;
+      o.x = (z0 && (mk[i] & 0xffu)) ? 0.f : old[i].x - t.x;
+      o.y = (z1 && (mk[i] >> 8)) ? 0.f : old[i].y - t.y;
+      *reinterpret_cast<float2*>(Wg + (int64_t)row * a.b) = o;
+    }
+  } else {
+    for (int i = 0; i < 16; ++i) {
+      const int row = wave + 8 * i;
+      if (row >= m_ext) break;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = acc_row(wm, f, r, lane);
-        const bool ok = row < m_ext && col < n_ext;
-        const int64_t idx = (m0 + row) * a.b + cg;
-        old[r] = ok ? a.W[idx] : 0.f;
-        mk[r] = (ok && in_block && cg >= a.zj1 && cg < j2) ? (a.mask[idx] != 0) : false;
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = acc_row(wm, f, r, lane);
-        if (row < m_ext && col < n_ext) {
-          const int64_t idx = (m0 + row) * a.b + cg;
-          a.W[idx] = mk[r] ? 0.f : old[r] - acc.v[f][g][r];
+      for (int e = 0; e < 2; ++e) {
+        if (c0 + e < n_ext) {
+          const int64_t off = (int64_t)row * a.b + e;
+          const bool z = in_block && cg + e >= a.zj1 && cg + e < a.zj2 && Mg[off] != 0;
+          Wg[off] = z ? 0.f : Wg[off] - T[row * kXCLd + c0 + e];
         }
       }
     }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1553,6 +1566,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   }
 
   const bool aligned_b = (b % 4 == 0) && (B % 4 == 0);
+  const int pair_w = (aligned_b && reinterpret_cast<uintptr_t>(W) % 8 == 0 &&
+                      reinterpret_cast<uintptr_t>(mask) % 2 == 0) ? 1 : 0;
   {
     BlockRowsArgs a{U, w.P, b, B,
                     (aligned_b && reinterpret_cast<uintptr_t>(U) % 16 == 0) ? 1 : 0};
@@ -1650,7 +1665,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
 
     {  // this block's update, up to the end of its super-block
       UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
-                    (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+                    (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w};
       dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
       hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, s, ua);
       THANOS_LAUNCH_CHECK();
@@ -1662,7 +1677,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * sbi], s));
         THANOS_HIP_CHECK(hipStreamWaitEvent(aux.stream, aux.ev[2 * sbi], 0));
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w};
         dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
         hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, aux.stream, ua);
         THANOS_LAUNCH_CHECK();
@@ -1670,7 +1685,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
       {  // strip: the columns of the next super-block
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0};
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w};
         dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
         hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, s, ua);
         THANOS_LAUNCH_CHECK();
