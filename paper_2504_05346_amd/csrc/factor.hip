@@ -395,16 +395,7 @@ __global__ __launch_bounds__(kXThreads) void k_trinv_T(TrinvArgs a) {
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, tj * NB, a.S * NB, true, true);
-  if (threadIdx.x >= 256) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
-  float* C = a.T + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB;
-#pragma unroll
-  for (int f = 0; f < 2; ++f)
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        C[(int64_t)acc_row(wm, f, r, lane) * a.bp + acc_col(wn, g, lane)] = acc.v[f][g][r];
+  x3_write_tile(acc, sm, a.T + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB, a.bp, 1.f);
 }
 
 __global__ __launch_bounds__(kXThreads) void k_trinv_X(TrinvArgs a) {
@@ -418,16 +409,7 @@ __global__ __launch_bounds__(kXThreads) void k_trinv_X(TrinvArgs a) {
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<false, true>(acc, sm, A, a.bp, NB, B, a.bp, NB, 0, (ti + 1) * NB, true, true);
-  if (threadIdx.x >= 256) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
-  float* C = a.Linv + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB;
-#pragma unroll
-  for (int f = 0; f < 2; ++f)
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        C[(int64_t)acc_row(wm, f, r, lane) * a.bp + acc_col(wn, g, lane)] = -acc.v[f][g][r];
+  x3_write_tile(acc, sm, a.Linv + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB, a.bp, -1.f);
 }
 
 // U[i][j] = Linv[b-1-i][b-1-j] for j >= i, else 0.

@@ -313,4 +313,18 @@ __device__ __forceinline__ const float* x3_stage_tile(const TileAcc& acc, char* 
   return C;
 }
 
+// Whole, aligned tile: C[0:128, 0:128] = scale * acc (C 8-byte aligned, ldc even).  All 512 threads.
+__device__ __forceinline__ void x3_write_tile(const TileAcc& acc, char* smem, float* C,
+                                              int64_t ldc, float scale) {
+  const float* T = x3_stage_tile(acc, smem);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int row = wave + 8 * i;
+    const float2 t = *reinterpret_cast<const float2*>(T + row * kXCLd + 2 * lane);
+    *reinterpret_cast<float2*>(C + (int64_t)row * ldc + 2 * lane) =
+        make_float2(scale * t.x, scale * t.y);
+  }
+}
+
 }  // namespace thanos

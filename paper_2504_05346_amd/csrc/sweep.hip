@@ -101,20 +101,20 @@ __global__ __launch_bounds__(kXThreads) void k_block_rows(BlockRowsArgs a) {
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<true, true>(acc, sm, A, a.b, m_ext, Bm, a.b, n_ext, 0, bw, a.vec, a.vec);
-  if (threadIdx.x >= 256) return;  // producer wavefronts hold no result
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+  float* Pg = a.P + (j1 + mrow0) * a.b + col0;
+  if (m_ext == kTM && n_ext == kTN && a.vec) {  // P is 256-byte aligned, b and col0 multiples of 4
+    x3_write_tile(acc, sm, Pg, a.b, 1.f);
+    return;
+  }
+  const float* T = x3_stage_tile(acc, sm);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = 0; i < 16; ++i) {
+    const int row = wave + 8 * i;
+    if (row >= m_ext) break;
 #pragma unroll
-  for (int f = 0; f < 2; ++f)
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      const int col = acc_col(wn, g, lane);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = acc_row(wm, f, r, lane);
-        if (row < m_ext && col < n_ext)
-          a.P[(j1 + mrow0 + row) * a.b + col0 + col] = acc.v[f][g][r];
-      }
-    }
+    for (int e = 0; e < 2; ++e)
+      if (2 * lane + e < n_ext) Pg[(int64_t)row * a.b + 2 * lane + e] = T[row * kXCLd + 2 * lane + e];
+  }
 }
 
 // ------------------------------------------------------------------------------------------
