@@ -584,14 +584,26 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
   float u = (rho < s) ? wrow[qr] : 0.f;
   float dinv = 0.f;
   float A[SMAX];
+  // Loads are issued unconditionally, 16 at a time, from clamped (valid) indices and masked
+  // afterwards: a conditional load, or a select right behind a load, makes the compiler wait for
+  // every outstanding load, i.e. one memory round trip per element.  q * b < 2^31.
+  {
+    const unsigned int bb = (unsigned int)a.b, qc = (unsigned int)qr;
 #pragma unroll
-  for (int j = 0; j < SMAX; ++j) {
-    float v = 0.f;
-    if (j < s) {
-      const float* grow = G + (int64_t)q[j] * a.b;
-      if (rho < s) v = grow[qr];
+    for (int c16 = 0; c16 < SMAX / 16; ++c16) {
+      if (16 * c16 < s) {
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+          const int j = 16 * c16 + jj;
+          A[j] = G[(unsigned int)q[min(j, s - 1)] * bb + qc];
+        }
+      } else {
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) A[16 * c16 + jj] = 0.f;
+      }
     }
-    A[j] = v;
+#pragma unroll
+    for (int j = 0; j < SMAX; ++j) A[j] = (j < s && rho < s) ? A[j] : 0.f;
   }
 
   // ---- elimination ----
