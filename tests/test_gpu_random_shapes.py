@@ -1,0 +1,81 @@
+"""GPU parity on seeded random shapes, block sizes and modes.
+
+Every case draws (c, b, B, mode, n:m, p, alpha, dtype) from a seeded generator, so that block
+widths, ragged last blocks, alignment classes and the three per-row solvers (64 / 128 / 256
+unknowns) are hit in combinations the hand-written cases do not list.  Checks per case: the mask
+invariants of the mode, exact zeros, and W_hat against the oracle run under the GPU's own mask
+(1e-3 relative Frobenius error, the bar of test_gpu_prune.py; the masks themselves are compared
+bit by bit in the tests there, on inputs without near-ties).
+"""
+import numpy as np
+import pytest
+
+from oracle import thanos_oracle as orc
+from synth import LayerSpec, make_weight, make_calibration
+
+pytestmark = pytest.mark.gpu
+
+NM = [(2, 4), (4, 8), (1, 4), (3, 4), (1, 2), (5, 8), (2, 16)]
+
+
+def _draw(rng):
+    mode = str(rng.choice(["unstructured", "nm", "given", "structured"], p=[0.4, 0.35, 0.15, 0.1]))
+    c = int(rng.integers(1, 300))
+    if mode == "nm":
+        n, m = NM[int(rng.integers(0, len(NM)))]
+        B = int(m * rng.integers(1, 512 // m + 1))
+        if B // m * n > 256:
+            B = (256 // n) * m                      # at most 256 unknowns per row and block
+        b = int(m * rng.integers(max(1, B // m // 2), 3 * B // m + 2))
+        b = min(b, (1400 // m) * m)
+    else:
+        n = m = 0
+        B = int(rng.integers(1, 257))
+        b = min(int(rng.integers(max(2, B // 2), 3 * B + 2)), 1400)
+    dtype = str(rng.choice(["f32", "f16"]))
+    p = float(rng.choice([0.1, 0.3, 0.5, 0.6, 0.9]))
+    alpha = float(rng.choice([0.0, 0.0, 0.1, 0.3])) if mode in ("nm", "structured") else 0.0
+    rho = float(rng.choice([0.0, 0.7]))
+    seed = int(rng.integers(0, 1 << 30))
+    return mode, c, b, B, n, m, p, alpha, dtype, rho, seed
+
+
+@pytest.mark.parametrize("case_seed", [11, 12, 13, 14])
+def test_random_cases(case_seed):
+    from tests.gpu_util import gpu_prune
+    rng = np.random.default_rng(case_seed)
+    for it in range(12):
+        mode, c, b, B, n, m, p, alpha, dtype, rho, seed = _draw(rng)
+        if mode == "structured" and p / (1.0 - alpha) >= 1.0:
+            continue
+        print(f"case {case_seed}/{it}: {mode} c={c} b={b} B={B} {n}:{m} p={p} alpha={alpha} "
+              f"{dtype} rho={rho}", flush=True)
+        spec = LayerSpec("t", c=c, b=b, tokens=max(2 * b, 64), dtype=dtype, rho=rho, k_mix=8,
+                         seed=seed)
+        W, X = make_weight(spec), make_calibration(spec)
+        H32 = orc.hessian(X).astype(np.float32)
+        H = H32.astype(np.float64)
+        if mode == "unstructured":
+            Wg, Mg, info = gpu_prune(W, H32, mode=mode, p=p, B=B)
+            assert int(Mg.sum()) == orc.num_to_remove(p, c, b)
+            Wt, _ = orc.prune_fast(W, H, mode="unstructured", p=p, B=B, damp=0.01, mask_in=Mg)
+        elif mode == "given":
+            Mi = (rng.random((c, b)) < p).astype(np.uint8)
+            Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=B, mask_in=Mi)
+            np.testing.assert_array_equal(Mg, Mi)
+            Wt, _ = orc.prune_fast(W, H, mode="unstructured", p=0.5, B=B, damp=0.01, mask_in=Mi)
+        elif mode == "nm":
+            Wg, Mg, info = gpu_prune(W, H32, mode="nm", n=n, m=m, B=B, alpha=alpha)
+            rows = np.flatnonzero(Mg.any(axis=1))
+            assert len(rows) == c - orc.num_outlier_rows(alpha, c)
+            assert np.all(Mg[rows].reshape(len(rows), b // m, m).sum(axis=2) == n)
+            Wt, _ = orc.prune_fast(W, H, mode="nm", n=n, m=m, B=B, damp=0.01, mask_in=Mg)
+        else:
+            Wg, Mg, info = gpu_prune(W, H32, mode="structured", p=p, alpha=alpha)
+            Wt, Mo = orc.prune_structured(W, H, p, alpha, 0.01)
+            assert Mg.sum() == Mo.sum()
+            if not np.array_equal(Mg, Mo):          # a near-tie in the column or row ranking
+                continue
+        assert info == 0
+        assert np.all(Wg[Mg == 1] == 0.0)
+        assert np.linalg.norm(Wg - Wt) <= 1e-3 * max(np.linalg.norm(Wt), 1e-30)
