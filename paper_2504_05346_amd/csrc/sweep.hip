@@ -124,6 +124,7 @@ struct SelState {
   long long r_rem;      // weights still to remove (before the current block)
   long long rank;       // rank still to resolve inside the current prefix
   long long need_eq;    // how many keys equal to tau are removed (ties, in (row, col) order)
+  int ties_all;         // every key equal to tau is removed: no ranking of ties (need_eq = 2^62)
   unsigned int prefix;  // resolved high bits
   unsigned int tau;     // r-th smallest key
   int none;             // 1: nothing left to remove
@@ -356,6 +357,7 @@ __global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
   __shared__ long long part[256];
   __shared__ int sel_bin;
   __shared__ long long sel_before;
+  __shared__ unsigned int sel_count;
   const int tid = threadIdx.x;
   if (st->none) return;  // the histogram passes did not run either
   if (PASS < 2 && st->pred_ok) return;
@@ -384,6 +386,7 @@ __global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
     if (before < rank && rank <= before + loc[e]) {
       sel_bin = tid * 8 + e;
       sel_before = before;
+      sel_count = loc[e];
     }
     before += loc[e];
   }
@@ -393,8 +396,13 @@ __global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
     st->prefix = (st->prefix << bits) | (unsigned int)sel_bin;
     st->rank = rank - sel_before;
     if (PASS == 2) {
+      // The last pass resolves the key completely, so the chosen bin counts the keys equal to
+      // tau.  If all of them are removed (the usual case: one key at the threshold) their order
+      // does not matter and the two tie kernels have nothing to do.
+      const bool all = st->rank == (long long)sel_count;
       st->tau = st->prefix;
-      st->need_eq = st->rank;
+      st->need_eq = all ? (1ll << 62) : st->rank;
+      st->ties_all = all ? 1 : 0;
     }
   }
   for (int e = tid; e < 2048; e += 256) hist[e] = 0u;
@@ -410,6 +418,7 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave;
   if (i >= c) return;
+  if (st->ties_all) return;  // row_eq is not read: every tie passes the test against need_eq
   if (st->none || row_cand[i] == 0) {
     if (lane == 0) row_eq[i] = 0;
     return;
@@ -436,9 +445,11 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
 }
 
 // Exclusive prefix sum of row_eq over the rows (single workgroup, in place).
-__global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int64_t c) {
+__global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int64_t c,
+                                                   const SelState* __restrict__ st) {
   __shared__ long long part[1024];
   const int tid = threadIdx.x;
+  if (st->none || st->ties_all) return;
   const int64_t per = (c + 1023) / 1024;
   const int64_t lo = tid * per, hi = min(c, lo + per);
   long long s = 0;
@@ -1500,6 +1511,7 @@ __global__ void k_init_state(SelState* st, long long r) {
   st->r_rem = r;
   st->rank = 0;
   st->need_eq = 0;
+  st->ties_all = 0;
   st->prefix = 0u;
   st->tau = 0u;
   st->none = (r <= 0) ? 1 : 0;
@@ -1642,7 +1654,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       hipLaunchKernelGGL(k_sel_scan<2>, dim3(1), dim3(256), 0, s, w.st, w.hist);
       hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
                          w.row_cand, w.row_eq, sel_vec);
-      hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c);
+      hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c, w.st);
       THANOS_LAUNCH_CHECK();
     }
     SolveArgs sa;
