@@ -384,7 +384,7 @@ struct TrinvArgs {
   int nb, S;
 };
 
-__global__ __launch_bounds__(kXThreads) void k_trinv_T(TrinvArgs a) {
+__global__ __launch_bounds__(kXThreads, 4) void k_trinv_T(TrinvArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
   const int base = 2 * p * a.S;
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(kXThreads) void k_trinv_T(TrinvArgs a) {
   x3_write_tile(acc, sm, a.T + ((int64_t)gi * NB) * a.bp + (int64_t)gj * NB, a.bp, 1.f);
 }
 
-__global__ __launch_bounds__(kXThreads) void k_trinv_X(TrinvArgs a) {
+__global__ __launch_bounds__(kXThreads, 4) void k_trinv_X(TrinvArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
   const int base = 2 * p * a.S;

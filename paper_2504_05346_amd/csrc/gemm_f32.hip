@@ -16,7 +16,7 @@ struct GemmArgs {
 };
 
 template <bool AK, bool BK>
-__global__ __launch_bounds__(kXThreads) void k_gemm_f32(GemmArgs g) {
+__global__ __launch_bounds__(kXThreads, 4) void k_gemm_f32(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   const int tn = blockIdx.x, tm = blockIdx.y;
   if (g.lower_only && tn > tm) return;

@@ -8,16 +8,20 @@
 // 2^-24 |a||b|, the size of one fp32 rounding.  Six bf16 MFMAs of 32 cycles replace eight fp32
 // MFMAs (32x32x2) of 64 cycles for the same 32x32x16 block of products, and draw less power.
 //
-// One workgroup of 512 threads = 8 wavefronts, two per SIMD, with different jobs (a wavefront
-// cannot overlap its own vector arithmetic with its own MFMAs, two wavefronts of a SIMD can):
+// One workgroup of 512 threads = 8 wavefronts with different jobs (a wavefront cannot overlap
+// its own vector arithmetic with its own MFMAs, two wavefronts of a SIMD can):
 //   wavefronts 0..3 (consumers): 2x2 arrangement, each owns 64x64 = 2x2 MFMA tiles of the
 //       accumulator (same layout as gemm_tile.h); per slab of 32 k-values they read their
 //       operands from LDS (16 bytes per lane and fragment) and issue 48 MFMAs;
 //   wavefronts 4..7 (producers): 4,5 fetch the A slab, 6,7 the B slab (32 floats per thread),
 //       split them in registers and store three bf16 planes per operand in LDS as
 //       [row][32 k] (row stride 80 bytes: the 16-byte reads of consecutive rows then cover all
-//       banks).  Global loads run two slabs ahead of the multiplication.
-// Two LDS buffers, one barrier per slab.  After the call only wavefronts 0..3 hold the result.
+//       banks).  The global loads of the next slab are issued right after the stores.
+// One LDS buffer of 60 KB and two barriers per slab (filled / consumed): inside a workgroup
+// filling and multiplying alternate, and the overlap comes from the SECOND workgroup that the
+// small footprint (<= 128 registers, 68 KB of LDS with the staged write-out) lets a compute unit
+// hold.  Two buffers in one workgroup per unit (122 KB) were 15 % slower on large products:
+// every barrier stalled the whole unit.  After the call only wavefronts 0..3 hold the result.
 #pragma once
 #include "gemm_tile.h"
 
@@ -27,9 +31,11 @@ constexpr int kXK = 32;                      // k-values per slab
 constexpr int kXRow = 80;                    // bytes per LDS row: 32 bf16 + 16 bytes of padding
 constexpr int kXPlane = 128 * kXRow;         // one bf16 plane of one operand
 constexpr int kXThreads = 512;
-constexpr size_t kXSmemBytes = 2 * 6 * (size_t)kXPlane;  // 122 880
+// LDS of a workgroup: the six operand planes of one slab (61 440 bytes), reused for the staged
+// output tile (128 rows of 544 bytes), whichever is larger
+constexpr size_t kXSmemBytes = (6 * (size_t)kXPlane > 128 * 544) ? 6 * (size_t)kXPlane : 128 * 544;
 
-// LDS view: buf[2] x {a, b} x plane[3]
+// LDS view: {a, b} x plane[3] (buf is always 0: one buffer)
 __device__ __forceinline__ char* x3_plane(char* smem, int buf, int operand, int plane) {
   return smem + ((buf * 2 + operand) * 3 + plane) * kXPlane;
 }
@@ -182,29 +188,21 @@ __device__ __forceinline__ void slab_store_x3(char* smem, int buf, int operand,
   }
 }
 
-// Producer loop of one operand: load slabs two ahead, split and store them into the two LDS
-// buffers in turn, one barrier per slab (the consumers run the same barrier sequence).
+// Producer loop of one operand: split and store slab `it`, request slab `it + 1`, then the two
+// barriers of the slab (the consumers run the same barrier sequence).
 template <bool KMAJOR, bool FAST, bool MASKED>
 __device__ __forceinline__ void x3_produce(char* smem, int operand, const float* __restrict__ P,
                                            int64_t ld, int ext, int kbeg, int kend, int nslab,
                                            int u) {
   SlabSrcX3 src;
   slab_src_x3<KMAJOR>(src, P, ld, ext, kbeg, u);
-  SlabRegsX3 r0, r1;
-  slab_load_x3<KMAJOR, FAST>(r0, src, 0, kend - kbeg, P);
-  slab_load_x3<KMAJOR, FAST>(r1, src, 1, kend - kbeg - kXK, P);
-  slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r0, u);
-  __syncthreads();  // slab 0 is in buffer 0
-  for (int it = 0; it < nslab; it += 2) {
-    // consumers multiply slab `it` from buffer 0
-    slab_load_x3<KMAJOR, FAST>(r0, src, it + 2, kend - kbeg - (it + 2) * kXK, P);
-    if (it + 1 < nslab) slab_store_x3<KMAJOR, MASKED>(smem, 1, operand, r1, u);
-    __syncthreads();
-    if (it + 1 >= nslab) break;
-    // consumers multiply slab `it + 1` from buffer 1
-    slab_load_x3<KMAJOR, FAST>(r1, src, it + 3, kend - kbeg - (it + 3) * kXK, P);
-    if (it + 2 < nslab) slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r0, u);
-    __syncthreads();
+  SlabRegsX3 r;
+  slab_load_x3<KMAJOR, FAST>(r, src, 0, kend - kbeg, P);
+  for (int it = 0; it < nslab; ++it) {
+    slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r, u);
+    slab_load_x3<KMAJOR, FAST>(r, src, it + 1, kend - kbeg - (it + 1) * kXK, P);
+    __syncthreads();  // slab it is in LDS
+    __syncthreads();  // consumers are done with it
   }
 }
 
@@ -273,13 +271,10 @@ __device__ __forceinline__ void gemm_tile_x3(TileAcc& acc, char* smem, const flo
                                                                     acc.v[f][g], 0, 0, 0);
       }
     };
-    __syncthreads();  // slab 0 is in buffer 0
-    for (int it = 0; it < nslab; it += 2) {
+    for (int it = 0; it < nslab; ++it) {
+      __syncthreads();  // slab it is in LDS
       compute(0);
-      __syncthreads();
-      if (it + 1 >= nslab) break;
-      compute(1);
-      __syncthreads();
+      __syncthreads();  // done with it
     }
   }
 }

@@ -87,7 +87,7 @@ struct BlockRowsArgs {
   int vec;
 };
 
-__global__ __launch_bounds__(kXThreads) void k_block_rows(BlockRowsArgs a) {
+__global__ __launch_bounds__(kXThreads, 4) void k_block_rows(BlockRowsArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   const int64_t j1 = (int64_t)blockIdx.y * a.B;
   const int bw = (int)min((int64_t)a.B, a.b - j1);
@@ -1318,7 +1318,7 @@ struct UpdateArgs {
   int vec_w;            // W 8-byte and mask 2-byte aligned, b and col0 even: row pass in pairs
 };
 
-__global__ __launch_bounds__(kXThreads) void k_update(UpdateArgs a) {
+__global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   const int64_t m0 = (int64_t)blockIdx.y * kTM;
   const int64_t n0 = a.col0 + (int64_t)blockIdx.x * kTN;
