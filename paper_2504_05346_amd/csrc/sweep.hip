@@ -706,7 +706,7 @@ struct SolveMfmaSmem {
   float L[2016 + 64];  // strict lower triangle of L~, packed by rows: L~[m][k] at m(m-1)/2 + k
   float wrow[128];   // this row's weights of the block, later its lambdas
   float key[128];    // metric of the block (n:m ranking)
-  int q[128];
+  unsigned char q[128];  // block columns of the unknowns (block width <= 128)
   float dummy[160];  // where the lanes that hold nothing of a column write
 };
 
@@ -794,7 +794,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
     const int col = lane + 64 * r;
-    if (sel[r]) sm.q[myrank[r]] = col;
+    if (sel[r]) sm.q[myrank[r]] = (unsigned char)col;
     if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[r] ? 1 : 0;
   }
   if (SEL == SEL_THRESHOLD) {
