@@ -276,16 +276,18 @@ def test_factor_reuse_matches_internal_factor():
 
 
 # --------------------------------------------------------------------------- ties
-def test_exact_ties_follow_row_major_order():
+@pytest.mark.parametrize("B", [64, 128, 256])   # one block size per per-row solver
+def test_exact_ties_follow_row_major_order(B):
     # Diagonal Hessian: no surviving weight moves, so every block sees heavily tied metrics
     # (weights from a 5-value set); the mask must equal one global psi with (row, col) ties.
     from tests.gpu_util import gpu_prune
     g = np.random.default_rng(1)
-    c, b = 40, 256
+    c, b = 40, 512
     W = g.choice(np.array([-2.0, -1.0, 0.5, 1.0, 2.0], dtype=np.float32), size=(c, b))
     H32 = np.diag(g.choice(np.array([1.0, 4.0], dtype=np.float32), size=b))
     for p in (0.5, 0.3):
-        Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=p, B=64, damp=0.01)
+        print(f"ties B={B} p={p}", flush=True)
+        Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=p, B=B, damp=0.01)
         assert info == 0
         Mref = orc.psi(W, np.diag(H32), orc.num_to_remove(p, c, b))
         np.testing.assert_array_equal(Mg, Mref)
