@@ -238,57 +238,9 @@ __global__ __launch_bounds__(256) void k_sel_begin(SelState* __restrict__ st, in
 }
 
 // Window pass: bin = (key >> 4) - win_lo for the 2048 prefixes of the window, keys below the
-// window are counted, keys above it ignored.  Few keys fall inside, so most wavefront
-// iterations skip the LDS atomics and the pass runs at memory speed.
-__global__ __launch_bounds__(256) void k_sel_win(const float* __restrict__ W, int64_t c, int64_t b,
-                                                 int64_t j1, const float* __restrict__ sx,
-                                                 const SelState* __restrict__ st,
-                                                 unsigned int* __restrict__ hist,
-                                                 unsigned int* __restrict__ below_part, int vec) {
-  __shared__ unsigned int h[2048];
-  __shared__ unsigned int nb_wave[4];
-  if (st->none || !st->pred_try) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int e = tid; e < 2048; e += 256) h[e] = 0u;
-  __syncthreads();
-  const unsigned int lo = st->win_lo;
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
-  if (i < c) {
-    const float* row = W + i * b;
-    unsigned int nb = 0;
-    auto count = [&](unsigned int key) {
-      const unsigned int p28 = key >> 4;
-      if (p28 < lo) ++nb;
-      else if (p28 - lo < 2048u) atomicAdd(&h[p28 - lo], 1u);
-    };
-    if (vec) {
-      const int64_t nvec = (b - j1) >> 2;
-      for (int64_t v = lane; v < nvec; v += 64) {
-        const int64_t j = j1 + 4 * v;
-        const float4 w4 = *reinterpret_cast<const float4*>(row + j);
-        const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
-        count(metric_key(w4.x, s4.x));
-        count(metric_key(w4.y, s4.y));
-        count(metric_key(w4.z, s4.z));
-        count(metric_key(w4.w, s4.w));
-      }
-      for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64) count(metric_key(row[j], sx[j]));
-    } else {
-      for (int64_t j = j1 + lane; j < b; j += 64) count(metric_key(row[j], sx[j]));
-    }
-    for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
-    if (lane == 0) nb_wave[wave] = nb;
-  } else if (lane == 0) {
-    nb_wave[wave] = 0u;
-  }
-  __syncthreads();
-  // one partial count per workgroup (summed by the scan): thousands of atomics on one
-  // address would cost more than the pass itself
-  if (tid == 0) below_part[blockIdx.x] = nb_wave[0] + nb_wave[1] + nb_wave[2] + nb_wave[3];
-  for (int e = tid; e < 2048; e += 256)
-    if (h[e]) atomicAdd(&hist[e], h[e]);
-}
-
+// window are counted, keys above it ignored.  It has no kernel of its own: k_update counts the
+// new weights of the columns right of the block while it writes them (one pass over the residual
+// less per block), after k_sel_begin has set the window for the next block.
 // If the rank lies inside the window: 28 bits of the key are resolved, the first two radix
 // passes are skipped and the last one resolves 4 bits.  Otherwise nothing is changed and all
 // three run.
@@ -1302,16 +1254,31 @@ struct UpdateArgs {
   int64_t zj1, zj2;
   int K, ldl, vec_a, vec_b;
   int vec_w;            // W 8-byte and mask 2-byte aligned, b and col0 even: row pass in pairs
+  // Unstructured mode: while the new weights are at hand, the columns right of the block are
+  // histogrammed for the NEXT block's selection (window around the current threshold, see
+  // k_sel_begin / k_sel_scan_win); hist == nullptr switches this off.
+  unsigned int* hist;         // 2048 bins, global
+  unsigned int* below_part;   // keys below the window, one count per workgroup
+  const SelState* st;
+  const float* sx;
 };
+
+constexpr size_t kUpdSmemBytes = kXSmemBytes + 2048 * sizeof(unsigned int) + 16 * sizeof(unsigned int);
 
 __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
+  unsigned int* hw = reinterpret_cast<unsigned int*>(sm + kXSmemBytes);  // window histogram
+  unsigned int* nb_wave = hw + 2048;
   const int64_t m0 = (int64_t)blockIdx.y * kTM;
   const int64_t n0 = a.col0 + (int64_t)blockIdx.x * kTN;
   const int m_ext = (int)min((int64_t)kTM, a.c - m0);
   const int n_ext = (int)min((int64_t)kTN, a.col_end - n0);
   const float* A = a.Lam + m0 * a.ldl;          // (m,k) at A[m*ldl + k]
   const float* Bm = a.P + a.prow0 * a.b + n0;   // (k,n) at B[k*b + n]
+  // does this tile feed the next selection?  (uniform per workgroup)
+  const bool win = a.hist != nullptr && !a.st->none && a.st->pred_try && n0 + n_ext > a.zj2;
+  if (win)
+    for (int e = threadIdx.x; e < 2048; e += kXThreads) hw[e] = 0u;  // barriers follow in the product
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
@@ -1323,9 +1290,19 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   const bool in_block = n0 < a.zj2 && n0 + kTN > a.zj1;  // tile overlaps the columns holding masks
   float* Wg = a.W + m0 * a.b + cg;
   const uint8_t* Mg = a.mask + m0 * a.b + cg;
+  // window count of one new weight (columns right of the block only)
+  const unsigned int wlo = win ? a.st->win_lo : 0u;
+  unsigned int nb = 0;
+  auto count = [&](float w, float sxj) {
+    const unsigned int p28 = metric_key(w, sxj) >> 4;
+    if (p28 < wlo) ++nb;
+    else if (p28 - wlo < 2048u) atomicAdd(&hw[p28 - wlo], 1u);
+  };
   if (m_ext == kTM && n_ext == kTN && a.vec_w) {  // whole tile, aligned pairs
     const bool z0 = in_block && cg >= a.zj1 && cg < a.zj2;
     const bool z1 = in_block && cg + 1 >= a.zj1 && cg + 1 < a.zj2;
+    const bool h0 = win && cg >= a.zj2, h1 = win && cg + 1 >= a.zj2;
+    const float sx0 = h0 ? a.sx[cg] : 0.f, sx1 = h1 ? a.sx[cg + 1] : 0.f;
     float2 old[16];
     unsigned short mk[16];
 #pragma unroll
@@ -1342,6 +1319,8 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
       o.x = (z0 && (mk[i] & 0xffu)) ? 0.f : old[i].x - t.x;
       o.y = (z1 && (mk[i] >> 8)) ? 0.f : old[i].y - t.y;
       *reinterpret_cast<float2*>(Wg + (int64_t)row * a.b) = o;
+      if (h0) count(o.x, sx0);
+      if (h1) count(o.y, sx1);
     }
   } else {
     for (int i = 0; i < 16; ++i) {
@@ -1352,11 +1331,27 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
         if (c0 + e < n_ext) {
           const int64_t off = (int64_t)row * a.b + e;
           const bool z = in_block && cg + e >= a.zj1 && cg + e < a.zj2 && Mg[off] != 0;
-          Wg[off] = z ? 0.f : Wg[off] - T[row * kXCLd + c0 + e];
+          const float o = z ? 0.f : Wg[off] - T[row * kXCLd + c0 + e];
+          Wg[off] = o;
+          if (win && cg + e >= a.zj2) count(o, a.sx[cg + e]);
         }
       }
     }
   }
+  if (a.hist == nullptr) return;
+  // one partial count of the keys below the window per workgroup (summed by k_sel_scan_win:
+  // thousands of atomics on one address would cost more than the pass), window bins by atomics
+  for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
+  if (lane == 0) nb_wave[wave] = nb;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned int t = 0;
+    for (int v = 0; v < kXThreads / 64; ++v) t += nb_wave[v];
+    a.below_part[blockIdx.y * gridDim.x + blockIdx.x] = t;
+  }
+  if (win)
+    for (int e = threadIdx.x; e < 2048; e += kXThreads)
+      if (hw[e]) atomicAdd(&a.hist[e], hw[e]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1437,6 +1432,7 @@ struct SweepWs {
   SelState* st;
   int* row_cand;
   int* row_eq;
+  unsigned int* below_part;  // one count per workgroup of the block update
   float* Hf;        // alpha > 0: symmetric copy of H, b x b
   float* T;         // alpha > 0: W * H, c x b
   float* h;         // alpha > 0: row losses, c
@@ -1463,6 +1459,7 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers) {
   n += align_up(2048 * 4, 256);                 // hist
   n += align_up(sizeof(SelState), 256);         // state
   n += 2 * align_up((size_t)c * 4, 256);        // row_cand, row_eq
+  n += align_up((size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4, 256);  // below_part
   if (outliers) {
     n += align_up((size_t)b * b * 4, 256);      // Hf
     n += align_up((size_t)c * b * 4, 256);      // T
@@ -1482,6 +1479,8 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers) {
   w.st = reinterpret_cast<SelState*>(carve(p, sizeof(SelState)));
   w.row_cand = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
   w.row_eq = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
+  w.below_part = reinterpret_cast<unsigned int*>(
+      carve(p, (size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4));
   w.Hf = w.T = w.h = nullptr;
   w.row_skip = nullptr;
   if (outliers) {
@@ -1587,7 +1586,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                                          (int)kXSmemBytes));
     THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_update),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kXSmemBytes));
+                                         (int)kUpdSmemBytes));
     hipLaunchKernelGGL(k_block_rows, grid, dim3(kXThreads), kXSmemBytes, s, a);
     THANOS_LAUNCH_CHECK();
   }
@@ -1610,6 +1609,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   AuxStream aux(super > 1 ? 2 * n_super : 0);
   if (super > 1 && !aux.ok) return THANOS_ERR_HIP;
   int pending_join = -1;
+  int win_parts = 0;  // workgroups of the previous block's update (partial counts to sum)
   for (int64_t j1 = 0; j1 < b; j1 += B) {
     const int bw = (int)std::min<int64_t>(B, b - j1);
     const int64_t blk = j1 / B;
@@ -1622,12 +1622,13 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       // 16-byte loads need W + i*b + j1 and sx + j1 aligned (W, sx come 256-byte aligned)
       const int sel_vec = (b % 4 == 0 && j1 % 4 == 0 &&
                            reinterpret_cast<uintptr_t>(W) % 16 == 0) ? 1 : 0;
-      hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(256), 0, s, w.st, j1 == 0 ? 1 : 0, w.row_cand, c);
-      if (j1 > 0) {
-        hipLaunchKernelGGL(k_sel_win, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st, w.hist,
-                           reinterpret_cast<unsigned int*>(w.row_cand), sel_vec);
-        hipLaunchKernelGGL(k_sel_scan_win, dim3(1), dim3(256), 0, s, w.st, w.hist,
-                           reinterpret_cast<const unsigned int*>(w.row_cand), (int)rows4);
+      // k_sel_begin of this block ran before the previous block's update, which then counted
+      // the window around the previous threshold while it wrote the new weights
+      if (j1 == 0) {
+        hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(256), 0, s, w.st, 1, w.row_cand, c);
+      } else {
+        hipLaunchKernelGGL(k_sel_scan_win, dim3(1), dim3(256), 0, s, w.st, w.hist, w.below_part,
+                           win_parts);
       }
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
                          w.hist, w.row_cand, sel_vec);
@@ -1673,10 +1674,16 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     THANOS_LAUNCH_CHECK();
 
     {  // this block's update, up to the end of its super-block
-      UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
-                    (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w};
       dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
-      hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, s, ua);
+      const bool feed = unstructured && j1 + bw < b;  // a next block exists: count its window
+      if (feed) {
+        hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(256), 0, s, w.st, 0, w.row_cand, c);
+        win_parts = (int)(grid.x * grid.y);
+      }
+      UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
+                    (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w,
+                    feed ? w.hist : nullptr, w.below_part, w.st, w.sx};
+      hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kUpdSmemBytes, s, ua);
       THANOS_LAUNCH_CHECK();
     }
     if (super > 1 && j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block
@@ -1686,17 +1693,19 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * sbi], s));
         THANOS_HIP_CHECK(hipStreamWaitEvent(aux.stream, aux.ev[2 * sbi], 0));
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w};
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
+                      nullptr};
         dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
-        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, aux.stream, ua);
+        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kUpdSmemBytes, aux.stream, ua);
         THANOS_LAUNCH_CHECK();
       }
       if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
       {  // strip: the columns of the next super-block
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w};
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
+                      nullptr};
         dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
-        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kXSmemBytes, s, ua);
+        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kUpdSmemBytes, s, ua);
         THANOS_LAUNCH_CHECK();
       }
       if (next_end < b) {
