@@ -440,6 +440,8 @@ struct SolveArgs {
   int64_t c, b, j1;
   int bw, ldl, n, m;
   int nt_lo, nt_max;     // k_solve_tiled: rows with nt_lo <= ceil(s/32) <= nt_max; LDS holds nt_max
+  int s_min;             // k_solve_wide: rows with s < s_min belong to another launch
+  int defer_large;       // k_solve_mfman: rows with more unknowns than it holds belong to another launch
 };
 
 // ------------------------------------------------------------------------------------------
@@ -512,6 +514,7 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
     if (v < wave) sel_before += cnt[v];
     s += cnt[v];
   }
+  if (s < a.s_min) return;  // solved by the launch for smaller systems
   const int myrank = sel_before + __popcll(bal & ((1ull << lane) - 1ull));
   if (sel) q[myrank] = tid;
   if (tid < a.bw) a.mask_out[i * a.b + a.j1 + tid] = sel ? 1 : 0;
@@ -872,6 +875,261 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   for (int r = 0; r < CPL; ++r) sm.wrow[lane + 64 * r] = 0.f;
   WAVE_SYNC();
   if (lane < s) sm.wrow[sm.q[lane]] = zz;
+  WAVE_SYNC();
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const int col = lane + 64 * r;
+    if (col < a.bw) lam_g[col] = sm.wrow[col];
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// The same one-wavefront-per-row elimination for up to NTR tile rows (s <= 32 NTR, block width
+// <= 128): the lower triangle of the tile grid is held in registers, diagonal tiles as they are,
+// tile (i, j), i > j, transposed (register r of lane (lo, hi) = R_hat[32 i + lo][32 j + row(r, hi)]),
+// so that column k of a tile below the pivot tile is again row k of the register tile.  A pivot
+// of tile row p costs one rank-1 MFMA per live tile (i, j), p <= j <= i.  NTR = 3 serves the
+// unstructured mode at B = 128, where s scatters around 64 and the 64-unknown kernel would
+// leave half of the rows to the much slower 128-thread kernel.
+template <int NTR>
+struct SolveMfmaNSmem {
+  static constexpr int N = 32 * NTR;
+  float L[N * (N - 1) / 2 + 64];  // strict lower triangle of L~, packed by rows
+  float wrow[128];
+  float key[128];
+  unsigned char q[128];
+  float dummy[128];
+};
+
+template <int SEL, int WPB, int NTR>
+__global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
+  constexpr int CPL = 2;  // block width <= 128
+  constexpr int NZ = (NTR + 1) / 2;  // registers holding y / d: rows 64 z + lane
+  extern __shared__ __attribute__((aligned(16))) char solve_smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  SolveMfmaNSmem<NTR>& sm = reinterpret_cast<SolveMfmaNSmem<NTR>*>(solve_smem)[wave];
+  const int lo = lane & 31, hi = lane >> 5;
+  const int64_t i = (int64_t)blockIdx.x * WPB + wave;
+  if (i >= a.c) return;
+  const float* wrow_g = a.W + i * a.b + a.j1;
+
+  // ---- selection of the block mask row M_i ----
+  bool sel[CPL];
+  float wv[CPL];
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const int col = lane + 64 * r;
+    wv[r] = (col < a.bw) ? wrow_g[col] : 0.f;
+    sm.wrow[col] = wv[r];
+    sel[r] = false;
+  }
+  if (SEL == SEL_GIVEN) {
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      sel[r] = (col < a.bw) && a.mask_in[i * a.b + a.j1 + col] != 0;
+    }
+  } else if (SEL == SEL_NM) {
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      sm.key[col] = (col < a.bw) ? fabsf(wv[r]) * a.sx[a.j1 + col] : 0.f;
+    }
+    WAVE_SYNC();
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      if (col < a.bw) {
+        const int g0 = (col / a.m) * a.m;
+        const float mine = sm.key[col];
+        int rank = 0;
+        for (int e = 0; e < a.m; ++e) {
+          const float o = sm.key[g0 + e];
+          rank += (o < mine || (o == mine && g0 + e < col)) ? 1 : 0;
+        }
+        sel[r] = rank < a.n;
+      }
+    }
+    if (a.row_skip && a.row_skip[i]) {
+#pragma unroll
+      for (int r = 0; r < CPL; ++r) sel[r] = false;
+    }
+  } else {  // SEL_THRESHOLD: key < tau, or key == tau and among the first need_eq ties
+    const bool none = a.st->none != 0;
+    const unsigned int tau = a.st->tau;
+    const long long need_eq = a.st->need_eq;
+    long long tie_rank = ties_before(a.st, a.row_eq, i, lane);
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      const bool in = (col < a.bw) && !none;
+      const unsigned int key = in ? metric_key(wv[r], a.sx[a.j1 + col]) : 0xffffffffu;
+      const bool lt = in && key < tau;
+      const bool eq = in && key == tau;
+      const unsigned long long eqb = __ballot(eq);
+      const long long my = tie_rank + __popcll(eqb & ((1ull << lane) - 1ull));
+      sel[r] = lt || (eq && my < need_eq);
+      tie_rank += __popcll(eqb);
+    }
+  }
+
+  // ---- q = phi(M_i) (ascending column indices) and s ----
+  int s = 0;
+  int myrank[CPL];
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const unsigned long long bal = __ballot(sel[r]);
+    myrank[r] = s + __popcll(bal & ((1ull << lane) - 1ull));
+    s += __popcll(bal);
+  }
+  if (s > 32 * NTR && a.defer_large) return;  // solved by the launch for larger systems
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) {
+    const int col = lane + 64 * r;
+    if (sel[r]) sm.q[myrank[r]] = (unsigned char)col;
+    if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[r] ? 1 : 0;
+  }
+  if (SEL == SEL_THRESHOLD) {
+    if (lane == 0) a.row_cnt[i] = s;  // summed at the start of the next block
+  }
+  float* lam_g = a.Lam + i * a.ldl;
+  if (s == 0 || s > 32 * NTR) {  // s > 32 NTR cannot happen for a launch chosen by the host
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      if (col < a.bw) lam_g[col] = 0.f;
+    }
+    return;
+  }
+  WAVE_SYNC();
+
+  // ---- gather R_hat = G[q, q] into the tiles (all loads unconditional from clamped, valid
+  //      indices, masked afterwards); right-hand side distributed by row ----
+  const float* G = a.P + a.j1 * a.b + a.j1;
+  const unsigned int bb = (unsigned int)a.b;  // q * b < 2^31
+  f32x16 T[NTR][NTR];
+  unsigned int qcol[NTR];
+#pragma unroll
+  for (int ti = 0; ti < NTR; ++ti) qcol[ti] = sm.q[min(32 * ti + lo, s - 1)];
+#pragma unroll
+  for (int tj = 0; tj < NTR; ++tj) {
+    if (32 * tj < s) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * hi + (r & 3);  // tile row held in register r
+        const unsigned int off = (unsigned int)sm.q[min(32 * tj + row, s - 1)] * bb;
+#pragma unroll
+        for (int ti = tj; ti < NTR; ++ti) T[ti][tj][r] = G[off + qcol[ti]];
+      }
+    }
+  }
+#pragma unroll
+  for (int tj = 0; tj < NTR; ++tj)
+#pragma unroll
+    for (int ti = tj; ti < NTR; ++ti)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * hi + (r & 3);
+        const float ident = (ti == tj && row == lo) ? 1.f : 0.f;  // identity outside the system
+        T[ti][tj][r] = (32 * tj + row < s && 32 * ti + lo < s) ? T[ti][tj][r] : ident;
+      }
+  // Each half of the wavefront only sees the pivots whose row it holds, so the value of a row of
+  // the right-hand side is the SUM of its two lanes (lo and lo + 32); it starts in the lower half.
+  float uv[NTR], zz[NZ];
+#pragma unroll
+  for (int ti = 0; ti < NTR; ++ti)
+    uv[ti] = (hi == 0 && 32 * ti + lo < s) ? sm.wrow[sm.q[min(32 * ti + lo, s - 1)]] : 0.f;
+#pragma unroll
+  for (int z = 0; z < NZ; ++z) zz[z] = 0.f;  // row 64 z + lane: y / d
+  const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
+  // where this lane's element of column k of L~ goes: row 32 ti + lo of the packed triangle;
+  // lanes that hold nothing of it, or an element on / above the diagonal, write to scratch
+  float* rowp[NTR];
+#pragma unroll
+  for (int ti = 0; ti < NTR; ++ti) rowp[ti] = &sm.L[(32 * ti + lo) * (32 * ti + lo - 1) / 2];
+  float* const junk = &sm.dummy[32 + lo];
+  bool bad = false;
+
+#pragma unroll
+  for (int p = 0; p < NTR; ++p) {
+    if (32 * p < s) {
+#pragma unroll
+      for (int k = 0; k < 32; ++k) {
+        if (32 * p + k < s) {
+          const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
+          const float d =
+              __int_as_float(__builtin_amdgcn_readlane(__float_as_int(T[p][p][rk]), k + 32 * hk));
+          const float yk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k)) +
+                           __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k + 32));
+          bad = bad || !(d > 0.f);
+          const float rd = __builtin_amdgcn_rcpf(d);
+          const float rdr = fmaf(fmaf(-d, rd, 1.f), rd, rd);
+          const float u = (key[hk] >= k) ? T[p][p][rk] : 0.f;  // row k = column k of the reduced tile
+          const float au = -rdr * u;
+          T[p][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, T[p][p], 0, 0, 0);
+          (key[hk] > k ? rowp[p] + 32 * p : junk)[k] = -au;   // L~[32p+k+1 : 32p+32, 32p+k]
+          const float au2 = (lo == k) ? 0.f : au;              // the pivot row itself stays
+          uv[p] = fmaf(au2, yk, uv[p]);
+          if (lane == ((32 * p + k) & 63)) zz[(32 * p + k) >> 6] = yk * rdr;
+          float ek[NTR], be[NTR];
+#pragma unroll
+          for (int ti = p + 1; ti < NTR; ++ti) {
+            if (32 * ti < s) {
+              ek[ti] = (key[hk] >= 0) ? T[ti][p][rk] : 0.f;  // R_hat[32 ti : 32 ti + 32, 32 p + k]
+              be[ti] = -rdr * ek[ti];
+              T[ti][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(u, be[ti], T[ti][p], 0, 0, 0);
+              (key[hk] >= 0 ? rowp[ti] + 32 * p : junk)[k] = -be[ti];
+              uv[ti] = fmaf(be[ti], yk, uv[ti]);
+#pragma unroll
+              for (int tj = p + 1; tj <= ti; ++tj) {
+                // transposed storage: the first operand runs over the rows of tile row tj
+                T[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(be[tj], ek[ti], T[ti][tj], 0, 0, 0);
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+  if (bad && lane == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
+  WAVE_SYNC();
+
+  // ---- L~^T lambda = z: lambda_k is final once all rows below it are done; then column k of
+  //      L~^T (= row k of L~, one LDS row) is swept out of the rows above.  The LDS rows of eight
+  //      unknowns are fetched together, ahead of the dependent chain. ----
+#pragma unroll
+  for (int k8 = 32 * NTR - 8; k8 >= 0; k8 -= 8) {
+    if (k8 < s) {
+      float row[8][NZ];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int k = k8 + t;
+#pragma unroll
+        for (int z = 0; z < NZ; ++z)  // lanes past the row read beyond it: masked below
+          row[t][z] = (64 * z < k) ? sm.L[k * (k - 1) / 2 + 64 * z + lane] : 0.f;
+      }
+#pragma unroll
+      for (int t = 7; t >= 0; --t) {
+        const int k = k8 + t;
+        if (k >= 1 && k < s) {
+          const float lk =
+              __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zz[k >> 6]), k & 63));
+#pragma unroll
+          for (int z = 0; z < NZ; ++z)
+            if (64 * z < k) zz[z] = fmaf(-((64 * z + lane < k) ? row[t][z] : 0.f), lk, zz[z]);
+        }
+      }
+    }
+  }
+
+  // ---- lambda row: zeros except lambda_l at column q_l ----
+#pragma unroll
+  for (int r = 0; r < CPL; ++r) sm.wrow[lane + 64 * r] = 0.f;
+  WAVE_SYNC();
+#pragma unroll
+  for (int z = 0; z < NZ; ++z)
+    if (64 * z + lane < s) sm.wrow[sm.q[64 * z + lane]] = zz[z];
   WAVE_SYNC();
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
@@ -1516,7 +1774,22 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb>), dim3((unsigned)ceil_div(a.c, kWpb)),
                        dim3(64 * kWpb), smem, s, a);
-  } else if (a.bw <= 128) {  // few tile rows: the register-resident kernel keeps more rows in flight
+  } else if (a.bw <= 128) {
+    // Up to 96 unknowns: one wavefront per row on the matrix cores.  When s varies from row to
+    // row (and may exceed 96) the few larger rows get a launch of the 128-thread kernel.
+    constexpr int kWpb = 2;
+    const size_t smem = kWpb * sizeof(SolveMfmaNSmem<3>);
+    const bool varies = SEL != SEL_NM;
+    if (varies || smax <= 96) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfman<SEL, kWpb, 3>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      a.defer_large = (varies && a.bw > 96) ? 1 : 0;
+      hipLaunchKernelGGL((k_solve_mfman<SEL, kWpb, 3>), dim3((unsigned)ceil_div(a.c, kWpb)),
+                         dim3(64 * kWpb), smem, s, a);
+      a.defer_large = 0;
+      if (!(varies && a.bw > 96)) return;
+      a.s_min = 97;
+    }
     hipLaunchKernelGGL((k_solve_wide<SEL, 128>), dim3((unsigned)a.c), dim3(128), 0, s, a);
   } else {
     // LDS per row grows with the square of the tile rows; systems of up to 160 unknowns leave
@@ -1664,6 +1937,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.n = o->n;
     sa.m = o->m;
     sa.nt_lo = sa.nt_max = 0;
+    sa.s_min = 0;
+    sa.defer_large = 0;
     if (o->mask_in) {
       launch_solve<SEL_GIVEN>(s, sa, bw);
     } else if (o->mode == THANOS_NM) {
