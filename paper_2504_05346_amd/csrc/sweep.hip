@@ -1004,6 +1004,16 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
   }
   WAVE_SYNC();
 
+  // ---- tile grid: nt tile rows, and the PARTIAL tile comes first.  Matrix index m < 32 - pad
+  //      is unknown m, 32 - pad <= m < 32 is padding (identity, never eliminated), m >= 32 is
+  //      unknown m - pad.  A pivot costs one MFMA per live tile, most in the first tile row
+  //      (NTR (NTR + 1) / 2 of them): with the short tile row in front, a system of 66 unknowns
+  //      costs 2 * 6 + 32 * 3 + 32 MFMAs instead of 32 * 6 + 32 * 3 + 2. ----
+  const int nt = (s + 31) >> 5;
+  const int pad = 32 * nt - s;
+  auto valid = [&](int m) { return m < 32 - pad || (m >= 32 && m - pad < s); };
+  auto unk = [&](int m) { return min(m < 32 ? m : m - pad, s - 1); };  // clamped: always a valid index
+
   // ---- gather R_hat = G[q, q] into the tiles (all loads unconditional from clamped, valid
   //      indices, masked afterwards); right-hand side distributed by row ----
   const float* G = a.P + a.j1 * a.b + a.j1;
@@ -1011,14 +1021,14 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
   f32x16 T[NTR][NTR];
   unsigned int qcol[NTR];
 #pragma unroll
-  for (int ti = 0; ti < NTR; ++ti) qcol[ti] = sm.q[min(32 * ti + lo, s - 1)];
+  for (int ti = 0; ti < NTR; ++ti) qcol[ti] = sm.q[unk(32 * ti + lo)];
 #pragma unroll
   for (int tj = 0; tj < NTR; ++tj) {
-    if (32 * tj < s) {
+    if (tj < nt) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = 8 * (r >> 2) + 4 * hi + (r & 3);  // tile row held in register r
-        const unsigned int off = (unsigned int)sm.q[min(32 * tj + row, s - 1)] * bb;
+        const unsigned int off = (unsigned int)sm.q[unk(32 * tj + row)] * bb;
 #pragma unroll
         for (int ti = tj; ti < NTR; ++ti) T[ti][tj][r] = G[off + qcol[ti]];
       }
@@ -1032,14 +1042,15 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
       for (int r = 0; r < 16; ++r) {
         const int row = 8 * (r >> 2) + 4 * hi + (r & 3);
         const float ident = (ti == tj && row == lo) ? 1.f : 0.f;  // identity outside the system
-        T[ti][tj][r] = (32 * tj + row < s && 32 * ti + lo < s) ? T[ti][tj][r] : ident;
+        T[ti][tj][r] = (tj < nt && ti < nt && valid(32 * tj + row) && valid(32 * ti + lo))
+                           ? T[ti][tj][r] : ident;
       }
   // Each half of the wavefront only sees the pivots whose row it holds, so the value of a row of
   // the right-hand side is the SUM of its two lanes (lo and lo + 32); it starts in the lower half.
   float uv[NTR], zz[NZ];
 #pragma unroll
   for (int ti = 0; ti < NTR; ++ti)
-    uv[ti] = (hi == 0 && 32 * ti + lo < s) ? sm.wrow[sm.q[min(32 * ti + lo, s - 1)]] : 0.f;
+    uv[ti] = (hi == 0 && ti < nt && valid(32 * ti + lo)) ? sm.wrow[sm.q[unk(32 * ti + lo)]] : 0.f;
 #pragma unroll
   for (int z = 0; z < NZ; ++z) zz[z] = 0.f;  // row 64 z + lane: y / d
   const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
@@ -1053,10 +1064,10 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
 
 #pragma unroll
   for (int p = 0; p < NTR; ++p) {
-    if (32 * p < s) {
+    if (p < nt) {
 #pragma unroll
       for (int k = 0; k < 32; ++k) {
-        if (32 * p + k < s) {
+        if (p > 0 || k < 32 - pad) {
           const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
           const float d =
               __int_as_float(__builtin_amdgcn_readlane(__float_as_int(T[p][p][rk]), k + 32 * hk));
@@ -1075,7 +1086,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
           float ek[NTR], be[NTR];
 #pragma unroll
           for (int ti = p + 1; ti < NTR; ++ti) {
-            if (32 * ti < s) {
+            if (ti < nt) {
               ek[ti] = (key[hk] >= 0) ? T[ti][p][rk] : 0.f;  // R_hat[32 ti : 32 ti + 32, 32 p + k]
               be[ti] = -rdr * ek[ti];
               T[ti][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(u, be[ti], T[ti][p], 0, 0, 0);
@@ -1100,7 +1111,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
   //      unknowns are fetched together, ahead of the dependent chain. ----
 #pragma unroll
   for (int k8 = 32 * NTR - 8; k8 >= 0; k8 -= 8) {
-    if (k8 < s) {
+    if (k8 < 32 * nt) {
       float row[8][NZ];
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
@@ -1112,7 +1123,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
 #pragma unroll
       for (int t = 7; t >= 0; --t) {
         const int k = k8 + t;
-        if (k >= 1 && k < s) {
+        if (k >= 1 && k < 32 * nt && valid(k)) {
           const float lk =
               __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zz[k >> 6]), k & 63));
 #pragma unroll
@@ -1129,7 +1140,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
   WAVE_SYNC();
 #pragma unroll
   for (int z = 0; z < NZ; ++z)
-    if (64 * z + lane < s) sm.wrow[sm.q[64 * z + lane]] = zz[z];
+    if (64 * z + lane < 32 * nt && valid(64 * z + lane)) sm.wrow[sm.q[unk(64 * z + lane)]] = zz[z];
   WAVE_SYNC();
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
