@@ -441,7 +441,7 @@ struct SolveArgs {
   int bw, ldl, n, m;
   int nt_lo, nt_max;     // k_solve_tiled: rows with nt_lo <= ceil(s/32) <= nt_max; LDS holds nt_max
   int s_min;             // k_solve_wide: rows with s < s_min belong to another launch
-  int defer_large;       // k_solve_mfman: rows with more unknowns than it holds belong to another launch
+  int defer_large;       // k_solve_mfma: rows with more unknowns than it holds belong to another launch
 };
 
 // ------------------------------------------------------------------------------------------
@@ -633,266 +633,21 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
 }
 
 // ------------------------------------------------------------------------------------------
-// Mask + per-row solve for systems of up to 64 unknowns on the matrix cores: one wavefront per
-// row of W, R_hat held in the accumulator layout of v_mfma_f32_32x32x2_f32 as three 32x32 tiles
-//   D0 = R_hat[0:32, 0:32],  E = R_hat[32:64, 0:32] (stored transposed),  D1 = R_hat[32:64, 32:64]
-// (identity on the unused part).  Symmetric elimination, square-root free (R_hat = L~ D L~^T):
+// Mask + per-row solve on the matrix cores for systems of up to 32 NTR unknowns (NTR = 2 or 3,
+// block width <= 128): one wavefront per row of W.  R_hat is held in the accumulator layout of
+// v_mfma_f32_32x32x2_f32 as the lower triangle of a grid of 32x32 tiles (identity on the unused
+// part): diagonal tiles as they are, tile (i, j), i > j, transposed (register r of lane (lo, hi)
+// = R_hat[32 i + lo][32 j + row(r, hi)]), so that column k of a tile below the pivot tile is
+// again row k of the register tile.  Symmetric elimination, square-root free (R_hat = L~ D L~^T):
 // row k of a symmetric tile in that layout is at once both operands of its rank-1 update, so a
-// pivot costs one MFMA per live tile and the only cross-lane traffic is the broadcast of the
-// pivot.  The right-hand side u is carried along (forward substitution: one FMA per tile and
-// pivot), column k of L~ goes to LDS, and L~^T lambda = D^-1 y is solved afterwards by column
-// sweeps that read one LDS row per unknown.
-struct SolveMfmaSmem {
-  float L[2016 + 64];  // strict lower triangle of L~, packed by rows: L~[m][k] at m(m-1)/2 + k
-  float wrow[128];   // this row's weights of the block, later its lambdas
-  float key[128];    // metric of the block (n:m ranking)
-  unsigned char q[128];  // block columns of the unknowns (block width <= 128)
-  float dummy[160];  // where the lanes that hold nothing of a column write
-};
-
-template <int SEL, int WPB>
-__global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
-  constexpr int CPL = 2;  // block width <= 128
-  extern __shared__ __attribute__((aligned(16))) char solve_smem[];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  SolveMfmaSmem& sm = reinterpret_cast<SolveMfmaSmem*>(solve_smem)[wave];
-  const int lo = lane & 31, hi = lane >> 5;
-  const int64_t i = (int64_t)blockIdx.x * WPB + wave;
-  if (i >= a.c) return;
-  const float* wrow_g = a.W + i * a.b + a.j1;
-
-  // ---- selection of the block mask row M_i ----
-  bool sel[CPL];
-  float wv[CPL];
-#pragma unroll
-  for (int r = 0; r < CPL; ++r) {
-    const int col = lane + 64 * r;
-    wv[r] = (col < a.bw) ? wrow_g[col] : 0.f;
-    sm.wrow[col] = wv[r];
-    sel[r] = false;
-  }
-  if (SEL == SEL_GIVEN) {
-#pragma unroll
-    for (int r = 0; r < CPL; ++r) {
-      const int col = lane + 64 * r;
-      sel[r] = (col < a.bw) && a.mask_in[i * a.b + a.j1 + col] != 0;
-    }
-  } else if (SEL == SEL_NM) {
-#pragma unroll
-    for (int r = 0; r < CPL; ++r) {
-      const int col = lane + 64 * r;
-      sm.key[col] = (col < a.bw) ? fabsf(wv[r]) * a.sx[a.j1 + col] : 0.f;
-    }
-    WAVE_SYNC();
-#pragma unroll
-    for (int r = 0; r < CPL; ++r) {
-      const int col = lane + 64 * r;
-      if (col < a.bw) {
-        const int g0 = (col / a.m) * a.m;
-        const float mine = sm.key[col];
-        int rank = 0;
-        for (int e = 0; e < a.m; ++e) {
-          const float o = sm.key[g0 + e];
-          rank += (o < mine || (o == mine && g0 + e < col)) ? 1 : 0;
-        }
-        sel[r] = rank < a.n;
-      }
-    }
-    if (a.row_skip && a.row_skip[i]) {
-#pragma unroll
-      for (int r = 0; r < CPL; ++r) sel[r] = false;
-    }
-  } else {  // SEL_THRESHOLD: key < tau, or key == tau and among the first need_eq ties
-    const bool none = a.st->none != 0;
-    const unsigned int tau = a.st->tau;
-    const long long need_eq = a.st->need_eq;
-    long long tie_rank = ties_before(a.st, a.row_eq, i, lane);
-#pragma unroll
-    for (int r = 0; r < CPL; ++r) {
-      const int col = lane + 64 * r;
-      const bool in = (col < a.bw) && !none;
-      const unsigned int key = in ? metric_key(wv[r], a.sx[a.j1 + col]) : 0xffffffffu;
-      const bool lt = in && key < tau;
-      const bool eq = in && key == tau;
-      const unsigned long long eqb = __ballot(eq);
-      const long long my = tie_rank + __popcll(eqb & ((1ull << lane) - 1ull));
-      sel[r] = lt || (eq && my < need_eq);
-      tie_rank += __popcll(eqb);
-    }
-  }
-
-  // ---- q = phi(M_i) (ascending column indices) and s ----
-  int s = 0;
-  int myrank[CPL];
-#pragma unroll
-  for (int r = 0; r < CPL; ++r) {
-    const unsigned long long bal = __ballot(sel[r]);
-    myrank[r] = s + __popcll(bal & ((1ull << lane) - 1ull));
-    s += __popcll(bal);
-  }
-#pragma unroll
-  for (int r = 0; r < CPL; ++r) {
-    const int col = lane + 64 * r;
-    if (sel[r]) sm.q[myrank[r]] = (unsigned char)col;
-    if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[r] ? 1 : 0;
-  }
-  if (SEL == SEL_THRESHOLD) {
-    if (lane == 0) a.row_cnt[i] = s;  // summed at the start of the next block
-  }
-  float* lam_g = a.Lam + i * a.ldl;
-  if (s == 0 || s > 64) {  // s > 64 cannot happen for a launch chosen by the host
-#pragma unroll
-    for (int r = 0; r < CPL; ++r) {
-      const int col = lane + 64 * r;
-      if (col < a.bw) lam_g[col] = 0.f;
-    }
-    return;
-  }
-  WAVE_SYNC();
-
-  // ---- gather R_hat = G[q, q] into the three tiles; u distributed by row ----
-  const float* G = a.P + a.j1 * a.b + a.j1;
-  const int q0 = (lo < s) ? sm.q[lo] : 0;            // column index of tile column lo
-  const int q1 = (32 + lo < s) ? sm.q[32 + lo] : 0;  // second tile
-  f32x16 D0, E, D1;
-  {
-    // All loads are issued unconditionally from clamped (valid) indices and masked afterwards:
-    // 48 independent loads in flight instead of 48 round trips.
-    float r0[16], re[16], r1[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = 8 * (r >> 2) + 4 * hi + (r & 3);  // tile row held in register r
-      const float* g0 = G + (int64_t)sm.q[min(row, s - 1)] * a.b;
-      const float* g1 = G + (int64_t)sm.q[min(32 + row, s - 1)] * a.b;
-      r0[r] = g0[q0];  // D0[row][lo]
-      re[r] = g0[q1];  // E[n = row][m = lo] = R_hat[32 + lo][row] = G[q[row]][q[32 + lo]]
-      r1[r] = g1[q1];  // D1[row][lo]
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = 8 * (r >> 2) + 4 * hi + (r & 3);
-      const float ident = (row == lo) ? 1.f : 0.f;  // identity outside the system
-      D0[r] = (row < s && lo < s) ? r0[r] : ident;
-      E[r] = (row < s && 32 + lo < s) ? re[r] : 0.f;
-      D1[r] = (32 + row < s && 32 + lo < s) ? r1[r] : ident;
-    }
-  }
-  // right-hand side: rows 0..31 in uv0, rows 32..63 in uv1.  Each half of the wavefront only
-  // sees the pivots whose row it holds, so the value of a row is the SUM of its two lanes
-  // (lane lo and lane lo + 32); the initial value lives in the lower half.
-  float uv0 = (hi == 0 && lo < s) ? sm.wrow[q0] : 0.f;
-  float uv1 = (hi == 0 && 32 + lo < s) ? sm.wrow[q1] : 0.f;
-  float zz = 0.f;  // lane l: y_l / d_l
-  const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
-  // where this lane's element of column k of L~ goes (rows lo and 32 + lo of the packed
-  // triangle); lanes that hold nothing of it, or an element on / above the diagonal, write to
-  // the scratch words
-  float* const row0 = &sm.L[lo * (lo - 1) / 2];
-  float* const row1 = &sm.L[(32 + lo) * (31 + lo) / 2];
-  float* const junk = &sm.dummy[32 + lo];
-  bool bad = false;
-  const bool two = s > 32;
-
-  // ---- pivots 0..31 ----
-#pragma unroll
-  for (int k = 0; k < 32; ++k) {
-    if (k < s) {
-      const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
-      const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(D0[rk]), k + 32 * hk));
-      const float yk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv0), k)) +
-                       __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv0), k + 32));
-      bad = bad || !(d > 0.f);
-      const float rd = __builtin_amdgcn_rcpf(d);
-      const float rdr = fmaf(fmaf(-d, rd, 1.f), rd, rd);
-      const float u = (key[hk] >= k) ? D0[rk] : 0.f;   // row k = column k of the reduced tile
-      const float au = -rdr * u;
-      D0 = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, D0, 0, 0, 0);
-      (key[hk] > k ? row0 : junk)[k] = -au;            // L~[k+1:32, k]
-      const float au2 = (lo == k) ? 0.f : au;          // the pivot row itself stays
-      uv0 = fmaf(au2, yk, uv0);
-      if (lane == k) zz = yk * rdr;
-      if (two) {
-        const float ek = (key[hk] >= 0) ? E[rk] : 0.f; // R_hat[32:64, k]
-        const float be = -rdr * ek;
-        E = __builtin_amdgcn_mfma_f32_32x32x2f32(u, be, E, 0, 0, 0);
-        D1 = __builtin_amdgcn_mfma_f32_32x32x2f32(be, ek, D1, 0, 0, 0);
-        (key[hk] >= 0 ? row1 : junk)[k] = -be;         // L~[32:64, k]
-        uv1 = fmaf(be, yk, uv1);
-      }
-    }
-  }
-  // ---- pivots 32..63 ----
-  if (two) {
-#pragma unroll
-    for (int k = 0; k < 32; ++k) {
-      if (32 + k < s) {
-        const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
-        const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(D1[rk]), k + 32 * hk));
-        const float yk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv1), k)) +
-                         __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv1), k + 32));
-        bad = bad || !(d > 0.f);
-        const float rd = __builtin_amdgcn_rcpf(d);
-        const float rdr = fmaf(fmaf(-d, rd, 1.f), rd, rd);
-        const float u = (key[hk] >= k) ? D1[rk] : 0.f;
-        const float au = -rdr * u;
-        D1 = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, D1, 0, 0, 0);
-        (key[hk] > k ? row1 + 32 : junk)[k] = -au;     // L~[32+k+1:64, 32 + k]
-        const float au2 = (lo == k) ? 0.f : au;
-        uv1 = fmaf(au2, yk, uv1);
-        if (lane == 32 + k) zz = yk * rdr;
-      }
-    }
-  }
-  if (bad && lane == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
-  WAVE_SYNC();
-
-  // ---- L~^T lambda = z: lambda_k is final once all rows below it are done; then column k of
-  //      L~^T (= row k of L~, one LDS row) is swept out of the rows above ----
-  // (the LDS rows of eight unknowns are fetched together, ahead of the dependent chain)
-#pragma unroll
-  for (int k8 = 56; k8 >= 0; k8 -= 8) {
-    if (k8 < s) {
-      float row[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int k = k8 + t;
-        row[t] = sm.L[k * (k - 1) / 2 + lane];  // lanes >= k read past the row: masked below
-      }
-#pragma unroll
-      for (int t = 7; t >= 0; --t) {
-        const int k = k8 + t;
-        if (k >= 1 && k < s) {
-          const float lk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zz), k));
-          zz = fmaf(-((lane < k) ? row[t] : 0.f), lk, zz);
-        }
-      }
-    }
-  }
-
-  // ---- lambda row: zeros except lambda_l at column q_l ----
-#pragma unroll
-  for (int r = 0; r < CPL; ++r) sm.wrow[lane + 64 * r] = 0.f;
-  WAVE_SYNC();
-  if (lane < s) sm.wrow[sm.q[lane]] = zz;
-  WAVE_SYNC();
-#pragma unroll
-  for (int r = 0; r < CPL; ++r) {
-    const int col = lane + 64 * r;
-    if (col < a.bw) lam_g[col] = sm.wrow[col];
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// The same one-wavefront-per-row elimination for up to NTR tile rows (s <= 32 NTR, block width
-// <= 128): the lower triangle of the tile grid is held in registers, diagonal tiles as they are,
-// tile (i, j), i > j, transposed (register r of lane (lo, hi) = R_hat[32 i + lo][32 j + row(r, hi)]),
-// so that column k of a tile below the pivot tile is again row k of the register tile.  A pivot
-// of tile row p costs one rank-1 MFMA per live tile (i, j), p <= j <= i.  NTR = 3 serves the
-// unstructured mode at B = 128, where s scatters around 64 and the 64-unknown kernel would
-// leave half of the rows to the much slower 128-thread kernel.
+// pivot of tile row p costs one MFMA per live tile (i, j), p <= j <= i, and the only cross-lane
+// traffic is the broadcast of the pivot.  The right-hand side u is carried along (forward
+// substitution: one FMA per tile row and pivot), column k of L~ goes to LDS, and
+// L~^T lambda = D^-1 y is solved afterwards by column sweeps that read one LDS row per unknown.
+// NTR = 2 serves n:m at B = 128 (s = 64 for 2:4 and 4:8); NTR = 3 the unstructured mode at
+// B = 128, where s scatters around 64.
 template <int NTR>
-struct SolveMfmaNSmem {
+struct SolveMfmaSmem {
   static constexpr int N = 32 * NTR;
   float L[N * (N - 1) / 2 + 64];  // strict lower triangle of L~, packed by rows
   float wrow[128];
@@ -902,13 +657,13 @@ struct SolveMfmaNSmem {
 };
 
 template <int SEL, int WPB, int NTR>
-__global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfman(SolveArgs a) {
+__global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   constexpr int CPL = 2;  // block width <= 128
   constexpr int NZ = (NTR + 1) / 2;  // registers holding y / d: rows 64 z + lane
   extern __shared__ __attribute__((aligned(16))) char solve_smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  SolveMfmaNSmem<NTR>& sm = reinterpret_cast<SolveMfmaNSmem<NTR>*>(solve_smem)[wave];
+  SolveMfmaSmem<NTR>& sm = reinterpret_cast<SolveMfmaSmem<NTR>*>(solve_smem)[wave];
   const int lo = lane & 31, hi = lane >> 5;
   const int64_t i = (int64_t)blockIdx.x * WPB + wave;
   if (i >= a.c) return;
@@ -1780,22 +1535,22 @@ template <int SEL>
 static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
   if (a.bw <= 128 && smax <= 64) {
     constexpr int kWpb = 4;
-    const size_t smem = kWpb * sizeof(SolveMfmaSmem);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfma<SEL, kWpb>),
+    const size_t smem = kWpb * sizeof(SolveMfmaSmem<2>);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfma<SEL, kWpb, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb>), dim3((unsigned)ceil_div(a.c, kWpb)),
+    hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb, 2>), dim3((unsigned)ceil_div(a.c, kWpb)),
                        dim3(64 * kWpb), smem, s, a);
   } else if (a.bw <= 128) {
     // Up to 96 unknowns: one wavefront per row on the matrix cores.  When s varies from row to
     // row (and may exceed 96) the few larger rows get a launch of the 128-thread kernel.
     constexpr int kWpb = 2;
-    const size_t smem = kWpb * sizeof(SolveMfmaNSmem<3>);
+    const size_t smem = kWpb * sizeof(SolveMfmaSmem<3>);
     const bool varies = SEL != SEL_NM;
     if (varies || smax <= 96) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfman<SEL, kWpb, 3>),
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfma<SEL, kWpb, 3>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       a.defer_large = (varies && a.bw > 96) ? 1 : 0;
-      hipLaunchKernelGGL((k_solve_mfman<SEL, kWpb, 3>), dim3((unsigned)ceil_div(a.c, kWpb)),
+      hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb, 3>), dim3((unsigned)ceil_div(a.c, kWpb)),
                          dim3(64 * kWpb), smem, s, a);
       a.defer_large = 0;
       if (!(varies && a.bw > 96)) return;
