@@ -396,18 +396,41 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
   if (lane == 0) row_eq[i] = n;
 }
 
-// Number of keys equal to tau in the rows before row i (ties are taken in (row, column) order).
-// Only needed when some but not all keys at the threshold are removed, which is rare: every
-// wavefront that asks sums the per-row counts of k_tie_rows itself (at most c integers, from L2)
-// instead of a prefix-sum kernel in the chain of every block.
-__device__ __forceinline__ long long ties_before(const SelState* __restrict__ st,
-                                                 const int* __restrict__ row_eq, int64_t i,
-                                                 int lane) {
-  if (st->none || st->ties_all) return 0;
+// Exclusive prefix sum of row_eq over the rows (single workgroup, in place): afterwards
+// row_eq[i] = number of keys equal to tau in the rows before row i (ties are taken in
+// (row, column) order).  Nothing to do when every key at the threshold is removed.
+__global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int64_t c,
+                                                   const SelState* __restrict__ st) {
+  __shared__ long long part[1024];
+  const int tid = threadIdx.x;
+  if (st->none || st->ties_all) return;
+  const int64_t per = (c + 1023) / 1024;
+  const int64_t lo = tid * per, hi = min(c, lo + per);
   long long s = 0;
-  for (int64_t r = lane; r < i; r += 64) s += row_eq[r];
-  for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-  return __shfl(s, 0, 64);
+  for (int64_t i = lo; i < hi; ++i) s += row_eq[i];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    long long run = 0;
+    for (int t = 0; t < 1024; ++t) {
+      const long long v = part[t];
+      part[t] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  long long run = part[tid];
+  for (int64_t i = lo; i < hi; ++i) {
+    const int v = row_eq[i];
+    row_eq[i] = (int)min(run, (long long)0x7fffffff);
+    run += v;
+  }
+}
+
+// Ties before row i; row_eq is stale (and not read) when no tie needs ranking.
+__device__ __forceinline__ long long ties_before(const SelState* __restrict__ st,
+                                                 const int* __restrict__ row_eq, int64_t i) {
+  return (st->none || st->ties_all) ? 0 : (long long)row_eq[i];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -433,7 +456,7 @@ struct SolveArgs {
   float* Lam;            // c x ldl
   const SelState* st;    // SEL_THRESHOLD
   SelState* st_rw;
-  const int* row_eq;     // keys equal to tau per row (k_tie_rows; see ties_before)
+  const int* row_eq;     // exclusive tie prefix per row (k_tie_rows + k_tie_scan; see ties_before)
   int* row_cnt;          // SEL_THRESHOLD: number of weights removed from row i in this block
   const uint8_t* row_skip;  // optional, c bytes: 1 = row is left untouched (outlier row)
   int32_t* info;
@@ -502,7 +525,7 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
     __syncthreads();
     int eq_before = 0;
     for (int v = 0; v < wave; ++v) eq_before += eqc[v];
-    const long long my = ties_before(a.st, a.row_eq, i, lane) + eq_before +
+    const long long my = ties_before(a.st, a.row_eq, i) + eq_before +
                          __popcll(eqb & ((1ull << lane) - 1ull));
     sel = lt || (eq && my < need_eq);
   }
@@ -714,7 +737,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
     const bool none = a.st->none != 0;
     const unsigned int tau = a.st->tau;
     const long long need_eq = a.st->need_eq;
-    long long tie_rank = ties_before(a.st, a.row_eq, i, lane);
+    long long tie_rank = ties_before(a.st, a.row_eq, i);
 #pragma unroll
     for (int r = 0; r < CPL; ++r) {
       const int col = lane + 64 * r;
@@ -1060,7 +1083,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
       if (lane == 0) eqc[NW * ch + wave] = __popcll(eqb[ch]);
     }
     __syncthreads();
-    const long long ties0 = ties_before(a.st, a.row_eq, i, lane);
+    const long long ties0 = ties_before(a.st, a.row_eq, i);
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) {
       long long my = ties0;
@@ -1680,6 +1703,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       hipLaunchKernelGGL(k_sel_scan<2>, dim3(1), dim3(256), 0, s, w.st, w.hist);
       hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
                          w.row_cand, w.row_eq, sel_vec);
+      hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c, w.st);
       THANOS_LAUNCH_CHECK();
     }
     SolveArgs sa;
