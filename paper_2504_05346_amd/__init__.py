@@ -18,3 +18,4 @@ from .binding import (  # noqa: F401
     thanos_prune_workspace_bytes,
     thanos_status_string,
 )
+from .layer_set import prune_layer_set  # noqa: F401,E402
