@@ -64,9 +64,12 @@ constexpr int kFactorNB = 128;  // block size of the blocked factorisation
 //   a_kmajor: element (m,k) of op(A) is A[k*lda + m], else A[m*lda + k]
 //   b_kmajor: element (k,n) of op(B) is B[k*ldb + n], else B[n*ldb + k]
 //   lower_only: compute only tiles with tile_row >= tile_col (C square)
+//   b_lower: op(B) (K x N, K == N) is lower triangular (zero for k < n): the reduction of an
+//            output tile starts at its first column
 thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, int64_t N,
                        int64_t K, float alpha, const float* A, int64_t lda, const float* B,
-                       int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only);
+                       int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only,
+                       bool b_lower = false);
 
 thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc,
                               thanos_dtype xdt, int64_t n_tok, int64_t ldx, float alpha);

@@ -13,6 +13,7 @@ struct GemmArgs {
   float alpha, beta;
   int lower_only;
   int vec_a, vec_b, vec_c;
+  int b_lower;  // op(B) is lower triangular: the reduction starts at the tile's first column
 };
 
 template <bool AK, bool BK>
@@ -26,7 +27,8 @@ __global__ __launch_bounds__(kXThreads, 4) void k_gemm_f32(GemmArgs g) {
   const float* B = BK ? g.B + n0 : g.B + (int64_t)n0 * g.ldb;
   TileAcc acc;
   acc_zero(acc);
-  gemm_tile_x3<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, 0, g.K, g.vec_a, g.vec_b);
+  gemm_tile_x3<AK, BK>(acc, sm, A, g.lda, m_ext, B, g.ldb, n_ext, g.b_lower ? n0 : 0, g.K, g.vec_a,
+                       g.vec_b);
   const float* T = x3_stage_tile(acc, sm);
   // row pass: wavefront w takes rows w, w + 8, ..., lane l the columns 2l, 2l + 1
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -66,11 +68,12 @@ static inline bool vec_ok(const float* p, int64_t ld) {
 
 thanos_status gemm_f32(hipStream_t s, bool a_kmajor, bool b_kmajor, int64_t M, int64_t N,
                        int64_t K, float alpha, const float* A, int64_t lda, const float* B,
-                       int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only) {
+                       int64_t ldb, float beta, float* C, int64_t ldc, bool lower_only,
+                       bool b_lower) {
   if (M <= 0 || N <= 0) return THANOS_OK;
   GemmArgs g{A, B, C, lda, ldb, ldc, (int)M, (int)N, (int)K, alpha, beta, lower_only ? 1 : 0,
              vec_ok(A, lda) ? 1 : 0, vec_ok(B, ldb) ? 1 : 0,
-             (reinterpret_cast<uintptr_t>(C) % 8 == 0 && ldc % 2 == 0) ? 1 : 0};
+             (reinterpret_cast<uintptr_t>(C) % 8 == 0 && ldc % 2 == 0) ? 1 : 0, b_lower ? 1 : 0};
   dim3 grid((unsigned)ceil_div(N, kTN), (unsigned)ceil_div(M, kTM));
   void (*kern)(GemmArgs);
   if (!a_kmajor && !b_kmajor) kern = k_gemm_f32<false, false>;

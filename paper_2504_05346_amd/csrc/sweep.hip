@@ -1404,29 +1404,19 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
 // ------------------------------------------------------------------------------------------
 // Outlier rows (App. G.4.4 / Sec. 4.7): h_i = ||W_i X||^2 = W_i H W_i^T; the ceil(alpha c) rows
 // with the largest h are left untouched.
-// Hf = symmetric copy of the lower triangle of H (32x32 tiles through LDS).
-__global__ __launch_bounds__(256) void k_mirror_lower(const float* __restrict__ H, int64_t b,
-                                                      float* __restrict__ Hf) {
-  __shared__ float t[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const int64_t i0 = (int64_t)blockIdx.y * 32, j0 = (int64_t)blockIdx.x * 32;
-  if (j0 > i0) return;  // tiles on and below the diagonal write themselves and their mirror
-  for (int r = ty; r < 32; r += 8) {
-    const int64_t i = i0 + r, j = j0 + tx;
-    float v = 0.f;
-    if (i < b && j < b) v = (j <= i) ? H[i * b + j] : H[j * b + i];
-    t[r][tx] = v;
-    if (i < b && j < b) Hf[i * b + j] = v;
-  }
-  __syncthreads();
-  if (i0 == j0) return;
-  for (int r = ty; r < 32; r += 8) {
-    const int64_t i = j0 + r, j = i0 + tx;  // mirrored tile
-    if (i < b && j < b) Hf[i * b + j] = t[tx][r];
-  }
+// W_i H W_i^T = 2 sum_n W_in sum_{k >= n} W_ik Hl_kn with Hl = the lower triangle of H with its
+// diagonal halved and zeros above it: the product T = W Hl only needs the reduction range
+// k >= n of every output column, i.e. half of the full product.
+__global__ __launch_bounds__(256) void k_lower_half_diag(const float* __restrict__ H, int64_t b,
+                                                         float* __restrict__ Hl) {
+  const int64_t i = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= b) return;
+  const float v = (j <= i) ? H[i * b + j] : 0.f;
+  Hl[i * b + j] = (j == i) ? 0.5f * v : v;
 }
 
-// h[i] = sum_j T[i][j] * W[i][j]; one wavefront per row, fp64 sum in a fixed order.
+// h[i] = 2 sum_j T[i][j] * W[i][j]; one wavefront per row, fp64 sum in a fixed order.
 __global__ __launch_bounds__(256) void k_rowdot(const float* __restrict__ T,
                                                 const float* __restrict__ W, int64_t c, int64_t b,
                                                 float* __restrict__ h) {
@@ -1436,7 +1426,7 @@ __global__ __launch_bounds__(256) void k_rowdot(const float* __restrict__ T,
   double acc = 0.0;
   for (int64_t j = lane; j < b; j += 64) acc += (double)T[i * b + j] * (double)W[i * b + j];
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-  if (lane == 0) h[i] = (float)acc;
+  if (lane == 0) h[i] = (float)(2.0 * acc);
 }
 
 // skip[i] = 1 for the n_out rows with the largest (h, row) (ascending order, ties by row index).
@@ -1454,13 +1444,14 @@ __global__ __launch_bounds__(256) void k_row_rank(const float* __restrict__ h, i
 }
 
 // skip[i] = 1 for the n_out rows of W (c x b fp32) with the largest loss W_i H W_i^T (H: lower
-// triangle).  Hf (b x b), T (c x b) and h (c) are scratch.
+// triangle).  Hf (b x b, receives the lower triangle with halved diagonal), T (c x b) and h (c)
+// are scratch.
 thanos_status row_outliers(hipStream_t s, const float* W, const float* H, int64_t c, int64_t b,
                            long long n_out, float* Hf, float* T, float* h, uint8_t* skip) {
-  hipLaunchKernelGGL(k_mirror_lower, dim3((unsigned)ceil_div(b, 32), (unsigned)ceil_div(b, 32)),
-                     dim3(256), 0, s, H, b, Hf);
+  hipLaunchKernelGGL(k_lower_half_diag, dim3((unsigned)ceil_div(b, 256), (unsigned)b), dim3(256), 0,
+                     s, H, b, Hf);
   THANOS_LAUNCH_CHECK();
-  thanos_status st = gemm_f32(s, false, true, c, b, b, 1.f, W, b, Hf, b, 0.f, T, b, false);
+  thanos_status st = gemm_f32(s, false, true, c, b, b, 1.f, W, b, Hf, b, 0.f, T, b, false, true);
   if (st != THANOS_OK) return st;
   hipLaunchKernelGGL(k_rowdot, dim3((unsigned)ceil_div(c, 4)), dim3(256), 0, s, T, W, c, b, h);
   THANOS_LAUNCH_CHECK();
