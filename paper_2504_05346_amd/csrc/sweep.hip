@@ -125,6 +125,7 @@ struct SelState {
   long long rank;       // rank still to resolve inside the current prefix
   long long need_eq;    // how many keys equal to tau are removed (ties, in (row, col) order)
   int ties_all;         // every key equal to tau is removed: no ranking of ties (need_eq = 2^62)
+  int deferred;         // 1: some row of the block was left to the second solver launch
   unsigned int prefix;  // resolved high bits
   unsigned int tau;     // r-th smallest key
   int none;             // 1: nothing left to remove
@@ -235,6 +236,7 @@ __global__ __launch_bounds__(256) void k_sel_begin(SelState* __restrict__ st, in
   st->below = 0ull;
   st->pred_ok = 0;
   st->shift = 10;
+  st->deferred = 0;
 }
 
 // Window pass: bin = (key >> 4) - win_lo for the 2048 prefixes of the window, keys below the
@@ -491,6 +493,8 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t i = blockIdx.x;
   const float* wrow_g = a.W + i * a.b + a.j1;
+  // second launch of a block (s_min > 0): nothing to do unless the first one left rows behind
+  if (SEL == SEL_THRESHOLD && a.s_min > 0 && a.st->deferred == 0) return;
 
   const float w = (tid < a.bw) ? wrow_g[tid] : 0.f;
   wrow[tid] = w;
@@ -761,7 +765,10 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
     myrank[r] = s + __popcll(bal & ((1ull << lane) - 1ull));
     s += __popcll(bal);
   }
-  if (s > 32 * NTR && a.defer_large) return;  // solved by the launch for larger systems
+  if (s > 32 * NTR && a.defer_large) {  // solved by the launch for larger systems
+    if (SEL == SEL_THRESHOLD && lane == 0) a.st_rw->deferred = 1;
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
     const int col = lane + 64 * r;
@@ -1535,6 +1542,7 @@ __global__ void k_init_state(SelState* st, long long r) {
   st->rank = 0;
   st->need_eq = 0;
   st->ties_all = 0;
+  st->deferred = 0;
   st->prefix = 0u;
   st->tau = 0u;
   st->none = (r <= 0) ? 1 : 0;

@@ -378,3 +378,27 @@ def test_singular_row_system_is_reported(B):
     ok = np.arange(c) != bad_row
     assert np.all(np.isfinite(Wg[ok]))
     assert np.all(Wg[ok][M[ok] == 1] == 0.0)
+
+
+@pytest.mark.parametrize("p", [0.72, 0.85])
+def test_block128_rows_split_between_two_solvers(p):
+    # B = 128 unstructured: rows with at most 96 removed weights in a block go to the
+    # one-wavefront matrix-core solver, the others to the 128-thread one.  p = 0.72 puts rows on
+    # both sides of that limit in every block, p = 0.85 nearly all of them above it.
+    from tests.gpu_util import gpu_prune
+    c, b = 192, 512
+    W, H32 = _layer(c, b, 2048, "f32", rho=0.7, seed=77)
+    print(f"split solvers p={p}", flush=True)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=p, B=128)
+    assert info == 0
+    assert int(Mg.sum()) == orc.num_to_remove(p, c, b)
+    per_block = Mg.reshape(c, b // 128, 128).sum(axis=2)
+    assert per_block.max() > 96
+    if p < 0.8:
+        assert per_block.min() <= 96
+    H = H32.astype(np.float64)
+    Wt, _ = orc.prune_fast(W, H, mode="unstructured", p=p, B=128, damp=0.01, mask_in=Mg)
+    assert np.all(Wg[Mg == 1] == 0.0)
+    assert _rel(Wg, Wt) < 1e-3
+    _, Mo = orc.prune_fast(W, H, mode="unstructured", p=p, B=128, damp=0.01)
+    assert (Mg != Mo).mean() < 1e-3
