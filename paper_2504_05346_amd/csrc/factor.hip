@@ -109,7 +109,12 @@ __global__ __launch_bounds__(256) void k_reverse_pad(const float* __restrict__ H
 //  * After the four steps: the off-diagonal blocks of the inverse by recursive doubling over
 //    32- and 64-blocks, X21 = -T22 (L21 T11), with the strict upper tiles of S as scratch.
 constexpr int kCdLd = NB + 1;  // LDS row stride in floats: conflict-free rows and columns
-constexpr size_t kCholDiagSmem = (2 * (size_t)NB * kCdLd + 4 * 128) * sizeof(float);
+// S: the block (lower triangle = L in the end, strict upper 32-tiles = scratch and, later, the
+// off-diagonal tiles (1,0) and (3,2) of the inverse); Td: the four diagonal 32x32 tiles of the
+// inverse side by side (32 rows); 128 floats of scratch per wavefront.  85 KB: the kernel fits
+// next to one workgroup of the matrix-product kernels on a compute unit instead of waiting for
+// a whole unit to drain.
+constexpr size_t kCholDiagSmem = ((size_t)(NB + 32) * kCdLd + 4 * 128) * sizeof(float);
 
 __device__ __forceinline__ int cd_row(int r, int hi) { return 8 * (r >> 2) + 4 * hi + (r & 3); }
 
@@ -202,7 +207,7 @@ __device__ __forceinline__ int cd_pivots(float* S, float* T, float* aux, int c0,
     aux[lo] = isd;
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-      T[(c0 + cd_row(r, hi)) * kCdLd + c0 + lo] = E[r] * aux[cd_row(r, hi)];
+      T[cd_row(r, hi) * kCdLd + c0 + lo] = E[r] * aux[cd_row(r, hi)];  // diagonal tile strip
   }
   return bad;
 }
@@ -215,10 +220,10 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
                                                       int32_t* __restrict__ info) {
   extern __shared__ __attribute__((aligned(16))) float cd_smem[];
   float* S = cd_smem;
-  float* T = cd_smem + NB * kCdLd;
+  float* T = cd_smem + NB * kCdLd;  // Td: tile j of the inverse's diagonal at T + 32 j
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float* aux = cd_smem + 2 * NB * kCdLd + 128 * wave;  // per-wavefront scratch
+  float* aux = cd_smem + (NB + 32) * kCdLd + 128 * wave;  // per-wavefront scratch
   const int lo = lane & 31, hi = lane >> 5;
   float* A = Ap + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
   float* Li = Linv + ((int64_t)kb_glob * NB) * bp + (int64_t)kb_glob * NB;
@@ -302,41 +307,49 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
     atomicCAS(info, 0, (int32_t)(orig > 0 ? orig : 1));
   }
 
-  // inverse, 32 -> 64: pairs (0,1) and (2,3); scratch = strict upper tile (p, p+1) of S
+  // inverse, 32 -> 64: pairs (0,1) and (2,3).  W = L21 T11 goes to the strict upper tile
+  // (p, p+1) of S and is then replaced, in place, by T21 = -T22 W (one wavefront, all operands
+  // are in registers before the result is stored).
   if (wave < 2) {
     const int p0 = 64 * wave, p1 = p0 + 32;
     f32x16 C;
 #pragma unroll
     for (int r = 0; r < 16; ++r) C[r] = 0.f;
-    cd_tile_mma32<true>(C, S + p1 * kCdLd + p0, T + p0 * kCdLd + p0, 1.f, lo, hi);
+    cd_tile_mma32<true>(C, S + p1 * kCdLd + p0, T + p0, 1.f, lo, hi);
     float* w = S + p0 * kCdLd + p1;
     cd_tile_store(w, C, 1.f, lo, hi);
 #pragma unroll
     for (int r = 0; r < 16; ++r) C[r] = 0.f;
-    cd_tile_mma32<true>(C, T + p1 * kCdLd + p1, w, 1.f, lo, hi);
-    cd_tile_store(T + p1 * kCdLd + p0, C, -1.f, lo, hi);
+    cd_tile_mma32<true>(C, T + p1, w, 1.f, lo, hi);
+    cd_tile_store(w, C, -1.f, lo, hi);  // tile (1,0) of the inverse at S[0:32, 32:64], (3,2) at S[64:96, 96:128]
   }
   __syncthreads();
   // 64 -> 128: W = L[64:128, 0:64] T[0:64, 0:64] into S[0:64, 64:128], then
-  // T[64:128, 0:64] = -T[64:128, 64:128] W; one 32x32 tile per wavefront.
+  // T[64:128, 0:64] = -T[64:128, 64:128] W straight to global memory; one 32x32 tile per
+  // wavefront.  Tile (a, b) of a 64x64 block of the inverse: diagonal ones in the strip, the
+  // off-diagonal one in S as stored above.
   {
     const int ti = wave >> 1, tj = wave & 1;  // tile inside the 64x64 block
     f32x16 C;
 #pragma unroll
     for (int r = 0; r < 16; ++r) C[r] = 0.f;
     // T[0:64,0:64] is lower triangular: 32-blocks of k from tj
-    for (int kb = tj; kb < 2; ++kb)
-      cd_tile_mma32<true>(C, S + (64 + 32 * ti) * kCdLd + 32 * kb,
-                          T + (32 * kb) * kCdLd + 32 * tj, 1.f, lo, hi);
+    for (int kb = tj; kb < 2; ++kb) {
+      const float* t11 = (kb == tj) ? T + 32 * kb : S + 32;  // tile (kb, tj) of T[0:64, 0:64]
+      cd_tile_mma32<true>(C, S + (64 + 32 * ti) * kCdLd + 32 * kb, t11, 1.f, lo, hi);
+    }
     cd_tile_store(S + (32 * ti) * kCdLd + 64 + 32 * tj, C, 1.f, lo, hi);
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 16; ++r) C[r] = 0.f;
     // T[64:128,64:128] is lower triangular: 32-blocks of k up to ti
-    for (int kb = 0; kb <= ti; ++kb)
-      cd_tile_mma32<true>(C, T + (64 + 32 * ti) * kCdLd + 64 + 32 * kb,
-                          S + (32 * kb) * kCdLd + 64 + 32 * tj, 1.f, lo, hi);
-    cd_tile_store(T + (64 + 32 * ti) * kCdLd + 32 * tj, C, -1.f, lo, hi);
+    for (int kb = 0; kb <= ti; ++kb) {
+      const float* t22 = (kb == ti) ? T + 64 + 32 * kb : S + 64 * kCdLd + 96;  // tile (ti, kb)
+      cd_tile_mma32<true>(C, t22, S + (32 * kb) * kCdLd + 64 + 32 * tj, 1.f, lo, hi);
+    }
+    float* g = Li + (int64_t)(64 + 32 * ti) * bp + 32 * tj;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) g[(int64_t)cd_row(r, hi) * bp + lo] = -C[r];
   }
   __syncthreads();
   {
@@ -348,9 +361,14 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
       float lv[4], tv[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const bool low = c4 + u <= i;
-        lv[u] = low ? S[i * kCdLd + c4 + u] : 0.f;
-        tv[u] = low ? T[i * kCdLd + c4 + u] : 0.f;
+        const int cc = c4 + u;
+        const bool low = cc <= i;
+        lv[u] = low ? S[i * kCdLd + cc] : 0.f;
+        // inverse: diagonal tiles from the strip, tiles (1,0) and (3,2) from the upper tiles of S
+        // (the lower left 64x64 quadrant is in global memory already and is skipped below)
+        const float* tp = ((i >> 5) == (cc >> 5)) ? T + (i & 31) * kCdLd + cc
+                                                  : S + (i - 32) * kCdLd + cc + 32;
+        tv[u] = (low && !(i >= 64 && cc < 64)) ? *tp : 0.f;
       }
       l[q] = make_float4(lv[0], lv[1], lv[2], lv[3]);
       t[q] = make_float4(tv[0], tv[1], tv[2], tv[3]);
@@ -366,7 +384,7 @@ __global__ __launch_bounds__(256, 2) void k_chol_diag(float* __restrict__ Ap,
         for (int u = 0; u < 4; ++u)
           if (c4 + u <= i) A[(int64_t)i * bp + c4 + u] = lv[u];
       }
-      *reinterpret_cast<float4*>(Li + (int64_t)i * bp + c4) = t[q];
+      if (!(i >= 64 && c4 < 64)) *reinterpret_cast<float4*>(Li + (int64_t)i * bp + c4) = t[q];
     }
   }
 }
