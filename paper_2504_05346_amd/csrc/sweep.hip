@@ -940,8 +940,9 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
 // of 32x32 tiles (padded with the identity past s) and factored by a right-looking blocked
 // Cholesky, R_hat = L L^T, 32 columns per step:
 //   1. one wavefront eliminates the diagonal tile with rank-1 MFMAs on its accumulator-layout
-//      copy (row k of a symmetric tile is both operands of D -= u u^T / d) and carries a second
-//      tile that starts as I along, which ends as T = L_pp^{-1}; T replaces the diagonal tile;
+//      copy (row k of a symmetric tile is both operands of D -= u u^T / d; two pivots per
+//      MFMA, see tl_pivots) and carries a second tile that starts as I along, which ends as
+//      T = L_pp^{-1} for a factor L_pp L_pp^T of the tile; T replaces the diagonal tile;
 //   2. the tiles below it become L_ip = A_ip T^T (one 32x32x32 product each), y_p = T u_p;
 //   3. the tiles right of the panel get A_il -= L_ip L_lp^T, the right-hand side u_i -= L_ip y_p;
 //      meanwhile one wavefront updates the next diagonal tile and runs step 1 on it (look-ahead:
@@ -975,35 +976,60 @@ __device__ __forceinline__ void tl_mma(f32x16& acc, const float* pa, const float
   for (int e = 0; e < 16; ++e)
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(sign * av[e], bv[e], acc, 0, 0, 0);
 }
-// Eliminates the symmetric tile D (accumulator layout) and writes T = L^{-1} (lower triangular,
-// zeros above the diagonal), L its Cholesky factor, to Dt.  One wavefront.  Returns true if a
-// pivot was not positive.
+// Eliminates the symmetric tile D (accumulator layout) and writes T = F^{-1}, F F^T = D, to Dt.
+// One wavefront.  Returns true if a pivot was not positive.
+//
+// Two pivots per MFMA.  In the accumulator layout rows k and k + 4 (k mod 8 < 4) sit in the same
+// register, in the lower and in the upper half of the wavefront: exactly where the two
+// reduction slots of v_mfma_f32_32x32x2_f32 take their operands from.  The pivots are therefore
+// taken in the order 0,4,1,5,2,6,3,7,8,12,...: with u1 = row k and u2 = row k + 4 AFTER the
+// elimination of k (u2 = D[k+4] - (D[k][k+4] / d1) u1; the lower half's row is fetched with one
+// cross-lane read), D -= u1 u1^T / d1 + u2 u2^T / d2 is one MFMA instead of two half-empty
+// ones.  The same row operations applied to a tile that starts as I give T~; F is the Cholesky
+// factor in that pivot order (a row-permuted triangle).  Nothing downstream needs a triangle:
+// the panel products, the substitutions and the trailing updates only use T as a dense tile.
 __device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int lo, int hi) {
   f32x16 E;
 #pragma unroll
   for (int r = 0; r < 16; ++r) E[r] = (tl_row(r, hi) == lo) ? 1.f : 0.f;
-  const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
-  float dl = 1.f;  // pivot of column lo
+  const int pidx = 4 * (lo >> 3) + (lo & 3);  // pair that eliminates column lo
+  float dl = 1.f;                             // pivot of column lo
 #pragma unroll
-  for (int k = 0; k < 32; ++k) {
-    const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
-    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(D[rk]), k + 32 * hk));
-    const float rd = __builtin_amdgcn_rcpf(d);
-    const float rdr = fmaf(fmaf(-d, rd, 1.f), rd, rd);
-    const float u = (key[hk] >= k) ? D[rk] : 0.f;  // row k = column k of the reduced tile
-    const float au = -rdr * u;
-    D = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, D, 0, 0, 0);
-    dl = (lo == k) ? d : dl;
-    const float ek = (key[hk] >= 0) ? E[rk] : 0.f;  // T~[k][:]
-    const float a2 = (lo == k) ? 0.f : au;          // row k itself stays
-    E = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, ek, E, 0, 0, 0);
+  for (int t = 0; t < 16; ++t) {              // pair t: rows k1 and k2 = k1 + 4, both in D[t]
+    const int k1 = 8 * (t >> 2) + (t & 3), k2 = k1 + 4;
+    const float v = D[t];                     // lower half: D[k1][lo], upper half: D[k2][lo]
+    const float x = __shfl(v, lo, 64);        // D[k1][lo] in both halves
+    const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k1));
+    const float c12 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k2));
+    const float d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32 + k2));
+    const float q1 = __builtin_amdgcn_rcpf(d1);
+    const float r1 = fmaf(fmaf(-d1, q1, 1.f), q1, q1);
+    const float m = c12 * r1;
+    const float d2p = fmaf(-c12, m, d2);      // pivot of k2 after the elimination of k1
+    const float q2 = __builtin_amdgcn_rcpf(d2p);
+    const float r2 = fmaf(fmaf(-d2p, q2, 1.f), q2, q2);
+    const float mh = hi ? m : 0.f;
+    // second operands: u1 in the lower half, u2 in the upper half; columns eliminated by
+    // earlier pairs are zero, and so is column k1 of u2
+    const bool live = pidx >= t && !(hi && lo == k1);
+    const float bop = live ? fmaf(-mh, x, v) : 0.f;
+    const float aop = bop * (hi ? -r2 : -r1);
+    D = __builtin_amdgcn_mfma_f32_32x32x2f32(aop, bop, D, 0, 0, 0);
+    dl = (lo == k1) ? d1 : (lo == k2) ? d2p : dl;
+    // the same row operations on T~: row k1 as it is, row k2 after the operation of k1; the
+    // pivot rows themselves stay
+    const float ev = E[t];
+    const float xe = __shfl(ev, lo, 64);
+    const float be = fmaf(-mh, xe, ev);
+    const float a2 = (lo == (hi ? k2 : k1)) ? 0.f : aop;
+    E = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, be, E, 0, 0, 0);
   }
   const bool bad = __ballot(!(dl > 0.f)) != 0ull;
   float isd = __builtin_amdgcn_rsqf(dl);
   isd = fmaf(0.5f * isd, fmaf(-dl * isd, isd, 1.f), isd);
   aux[lo] = isd;  // both halves write the same value
 #pragma unroll
-  for (int r = 0; r < 16; ++r)  // L^{-1} = diag(1/sqrt(d)) T~
+  for (int r = 0; r < 16; ++r)  // F^{-1} = diag(1/sqrt(d)) T~
     Dt[tl_row(r, hi) * kTlLd + lo] = E[r] * aux[tl_row(r, hi)];
   return bad;
 }
@@ -1203,7 +1229,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
 #pragma unroll
         for (int r = 0; r < 16; ++r) Aip[tl_row(r, hi) * kTlLd + lo] = C[r];
       }
-      if (wave == NW - 1 && lane < 32) {  // y_p = T u_p (T is zero above its diagonal)
+      if (wave == NW - 1 && lane < 32) {  // y_p = T u_p
         float acc = 0.f;
 #pragma unroll
         for (int k = 0; k < 32; ++k) acc = fmaf(Tp[lane * kTlLd + k], u[32 * p + k], acc);
