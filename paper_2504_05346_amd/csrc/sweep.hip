@@ -436,17 +436,10 @@ __device__ __forceinline__ long long ties_before(const SelState* __restrict__ st
 }
 
 // ------------------------------------------------------------------------------------------
-// Mask + per-row solve.  One wavefront per row of W.
-//
-// Solve lambda R_hat = u with R_hat = G[q, q] (symmetric positive definite, s x s, s <= 64*RPL).
-// Lane l owns rows l (and l+64) of R_hat in registers.  Elimination is Gauss-Jordan in its
-// symmetric form: at step k every row rho != k does  A[rho][j] -= l_rho * l_j  with
-// l = A[:, k] / sqrt(A[k][k]), which needs only the pivot COLUMN (each lane's own register)
-// broadcast to all lanes -- done through a small LDS buffer read back as aligned 16-byte
-// vectors.  Registers are indexed by (column - 4*panel): every fourth step writes its results
-// four registers lower, so the pivot columns of a panel are always registers 0..3 and the loop
-// over panels can stay rolled while all register indices are static.  After s steps
-// lambda_k = u_k / A[k][k] (pivot value at step k).
+// Mask + per-row solve (Alg. 1, loop over the rows of W; Sec. 4.1, eqs. (R_hat), (u)):
+// lambda R_hat = u with R_hat = G[q, q], G the block's rows of the residual inverse, q the
+// removed columns of the row (Sec. 4.5), u the removed weights.  Three kernels share the
+// arguments below and differ in how many unknowns they hold and where.
 enum { SEL_NM = 0, SEL_THRESHOLD = 1, SEL_GIVEN = 2 };
 
 struct SolveArgs {
@@ -666,10 +659,12 @@ __global__ __launch_bounds__(SMAX, (SMAX == 128 ? 3 : 1)) void k_solve_wide(Solv
 // part): diagonal tiles as they are, tile (i, j), i > j, transposed (register r of lane (lo, hi)
 // = R_hat[32 i + lo][32 j + row(r, hi)]), so that column k of a tile below the pivot tile is
 // again row k of the register tile.  Symmetric elimination, square-root free (R_hat = L~ D L~^T):
-// row k of a symmetric tile in that layout is at once both operands of its rank-1 update, so a
-// pivot of tile row p costs one MFMA per live tile (i, j), p <= j <= i, and the only cross-lane
-// traffic is the broadcast of the pivot.  The right-hand side u is carried along (forward
-// substitution: one FMA per tile row and pivot), column k of L~ goes to LDS, and
+// row k of a symmetric tile in that layout is at once both operands of its rank-1 update, and
+// rows k and k + 4 share a register (lower / upper half of the wavefront), so a PAIR of pivots
+// of tile row p costs one MFMA per live tile (i, j), p <= j <= i; the cross-lane traffic is the
+// broadcast of the pivots and one cross-lane read per tile row (the second pivot's row must
+// first see the elimination of the first).  The right-hand side u is carried along (forward
+// substitution: one FMA per tile row and pair), the columns of L~ go to LDS, and
 // L~^T lambda = D^-1 y is solved afterwards by column sweeps that read one LDS row per unknown.
 // NTR = 2 serves n:m at B = 128 (s = 64 for 2:4 and 4:8); NTR = 3 the unstructured mode at
 // B = 128, where s scatters around 64.
@@ -837,13 +832,20 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   for (int ti = 0; ti < NTR; ++ti)
     uv[ti] = (hi == 0 && ti < nt && valid(32 * ti + lo)) ? sm.wrow[sm.q[unk(32 * ti + lo)]] : 0.f;
 #pragma unroll
-  for (int z = 0; z < NZ; ++z) zz[z] = 0.f;  // row 64 z + lane: y / d
-  const int key[2] = {hi == 0 ? lo : -1, hi == 1 ? lo : -1};
-  // where this lane's element of column k of L~ goes: row 32 ti + lo of the packed triangle;
-  // lanes that hold nothing of it, or an element on / above the diagonal, write to scratch
+  for (int z = 0; z < NZ; ++z) zz[z] = 0.f;  // position 64 z + lane: y / d
+  // Two pivots per MFMA: rows k1 and k2 = k1 + 4 (k1 mod 8 < 4) of a tile sit in the same
+  // register, in the lower and in the upper half of the wavefront, where the two reduction slots
+  // of v_mfma_f32_32x32x2_f32 take their operands.  The pivots of a tile are therefore taken in
+  // the order 0,4,1,5,2,6,3,7,8,12,...; pair t = (k1, k2) holds POSITIONS 2t and 2t + 1 of that
+  // order.  L~ (unit lower triangular in elimination order), z and lambda are indexed by
+  // position; mrow() maps a position back to its matrix index.
+  const int pl = 8 * (lo >> 3) + 2 * (lo & 3) + ((lo >> 2) & 1);  // position of index lo in a tile
+  auto mrow = [](int P) { return (P & ~7) + ((P & 7) >> 1) + 4 * (P & 1); };
+  // where this lane's element of a column of L~ goes: the packed row of its position; lanes
+  // whose element is on / above the diagonal write to scratch
   float* rowp[NTR];
 #pragma unroll
-  for (int ti = 0; ti < NTR; ++ti) rowp[ti] = &sm.L[(32 * ti + lo) * (32 * ti + lo - 1) / 2];
+  for (int ti = 0; ti < NTR; ++ti) rowp[ti] = &sm.L[(32 * ti + pl) * (32 * ti + pl - 1) / 2];
   float* const junk = &sm.dummy[32 + lo];
   bool bad = false;
 
@@ -851,36 +853,57 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   for (int p = 0; p < NTR; ++p) {
     if (p < nt) {
 #pragma unroll
-      for (int k = 0; k < 32; ++k) {
-        if (p > 0 || k < 32 - pad) {
-          const int rk = 4 * (k >> 3) + (k & 3), hk = (k >> 2) & 1;
-          const float d =
-              __int_as_float(__builtin_amdgcn_readlane(__float_as_int(T[p][p][rk]), k + 32 * hk));
-          const float yk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k)) +
-                           __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k + 32));
-          bad = bad || !(d > 0.f);
-          const float rd = __builtin_amdgcn_rcpf(d);
-          const float rdr = fmaf(fmaf(-d, rd, 1.f), rd, rd);
-          const float u = (key[hk] >= k) ? T[p][p][rk] : 0.f;  // row k = column k of the reduced tile
-          const float au = -rdr * u;
-          T[p][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, T[p][p], 0, 0, 0);
-          (key[hk] > k ? rowp[p] + 32 * p : junk)[k] = -au;   // L~[32p+k+1 : 32p+32, 32p+k]
-          const float au2 = (lo == k) ? 0.f : au;              // the pivot row itself stays
-          uv[p] = fmaf(au2, yk, uv[p]);
-          if (lane == ((32 * p + k) & 63)) zz[(32 * p + k) >> 6] = yk * rdr;
-          float ek[NTR], be[NTR];
+      for (int t = 0; t < 16; ++t) {
+        const int k1 = 8 * (t >> 2) + (t & 3), k2 = k1 + 4;
+        if (p > 0 || k1 < 32 - pad) {  // a padding row paired with a real one is a no-op pivot
+          const float v = T[p][p][t];   // lower half: row k1 of the reduced tile, upper half: row k2
+          const float x = __shfl(v, lo, 64);
+          const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k1));
+          const float c12 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k2));
+          const float d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32 + k2));
+          const float y1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k1)) +
+                           __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k1 + 32));
+          const float y2r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k2)) +
+                            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(uv[p]), k2 + 32));
+          const float q1 = __builtin_amdgcn_rcpf(d1);
+          const float r1 = fmaf(fmaf(-d1, q1, 1.f), q1, q1);
+          const float m = c12 * r1;
+          const float d2p = fmaf(-c12, m, d2);  // pivot of k2 after the elimination of k1
+          const float q2 = __builtin_amdgcn_rcpf(d2p);
+          const float r2 = fmaf(fmaf(-d2p, q2, 1.f), q2, q2);
+          const float y2 = fmaf(-m, y1, y2r);
+          bad = bad || !(d1 > 0.f) || !(d2p > 0.f);
+          const float mh = hi ? m : 0.f;
+          const float rh = hi ? -r2 : -r1;
+          const float yh = hi ? y2 : y1;
+          // u1 (lower half) and u2 = row k2 after the elimination of k1 (upper half); columns
+          // eliminated earlier are zero, and so is column k1 of u2
+          const bool live = pl >= 2 * t && !(hi && lo == k1);
+          const float bop = live ? fmaf(-mh, x, v) : 0.f;
+          const float aop = bop * rh;
+          T[p][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(aop, bop, T[p][p], 0, 0, 0);
+          // column 2t + hi of L~ within the tile: rows at later positions
+          (pl > 2 * t + hi ? rowp[p] + 32 * p + hi : junk)[2 * t] = -aop;
+          const float a2 = (lo == (hi ? k2 : k1)) ? 0.f : aop;  // the pivot rows themselves stay
+          uv[p] = fmaf(a2, yh, uv[p]);
+          if ((lane >> 1) == (((32 * p + 2 * t) & 63) >> 1))
+            zz[(32 * p + 2 * t) >> 6] = (lane & 1) ? y2 * r2 : y1 * r1;
+          float e2[NTR], be[NTR];
 #pragma unroll
           for (int ti = p + 1; ti < NTR; ++ti) {
             if (ti < nt) {
-              ek[ti] = (key[hk] >= 0) ? T[ti][p][rk] : 0.f;  // R_hat[32 ti : 32 ti + 32, 32 p + k]
-              be[ti] = -rdr * ek[ti];
-              T[ti][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(u, be[ti], T[ti][p], 0, 0, 0);
-              (key[hk] >= 0 ? rowp[ti] + 32 * p : junk)[k] = -be[ti];
-              uv[ti] = fmaf(be[ti], yk, uv[ti]);
+              // R_hat[32 ti + lo][32 p + k1] (lower half) and [..][32 p + k2] (upper half)
+              const float ev = T[ti][p][t];
+              const float xe = __shfl(ev, lo, 64);
+              e2[ti] = fmaf(-mh, xe, ev);
+              be[ti] = rh * e2[ti];
+              T[ti][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(bop, be[ti], T[ti][p], 0, 0, 0);
+              (rowp[ti] + 32 * p + hi)[2 * t] = -be[ti];
+              uv[ti] = fmaf(be[ti], yh, uv[ti]);
 #pragma unroll
               for (int tj = p + 1; tj <= ti; ++tj) {
                 // transposed storage: the first operand runs over the rows of tile row tj
-                T[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(be[tj], ek[ti], T[ti][tj], 0, 0, 0);
+                T[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(be[tj], e2[ti], T[ti][tj], 0, 0, 0);
               }
             }
           }
@@ -908,7 +931,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
 #pragma unroll
       for (int t = 7; t >= 0; --t) {
         const int k = k8 + t;
-        if (k >= 1 && k < 32 * nt && valid(k)) {
+        if (k >= 1 && k < 32 * nt && valid(mrow(k))) {
           const float lk =
               __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zz[k >> 6]), k & 63));
 #pragma unroll
@@ -925,7 +948,8 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   WAVE_SYNC();
 #pragma unroll
   for (int z = 0; z < NZ; ++z)
-    if (64 * z + lane < 32 * nt && valid(64 * z + lane)) sm.wrow[sm.q[unk(64 * z + lane)]] = zz[z];
+    if (64 * z + lane < 32 * nt && valid(mrow(64 * z + lane)))
+      sm.wrow[sm.q[unk(mrow(64 * z + lane))]] = zz[z];
   WAVE_SYNC();
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
