@@ -400,11 +400,12 @@ struct TrinvArgs {
   float* T;
   int64_t bp;
   int nb, S;
+  int p0, c0;  // this launch: pairs from p0 (blockIdx.z), tile columns of a pair from c0 (blockIdx.x)
 };
 
 __global__ __launch_bounds__(kXThreads, 4) void k_trinv_T(TrinvArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
-  const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
+  const int tj = a.c0 + blockIdx.x, ti = blockIdx.y, p = a.p0 + blockIdx.z;
   const int base = 2 * p * a.S;
   const int gi = base + a.S + ti, gj = base + tj;
   if (gi >= a.nb) return;
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(kXThreads, 4) void k_trinv_T(TrinvArgs a) {
 
 __global__ __launch_bounds__(kXThreads, 4) void k_trinv_X(TrinvArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
-  const int tj = blockIdx.x, ti = blockIdx.y, p = blockIdx.z;
+  const int tj = a.c0 + blockIdx.x, ti = blockIdx.y, p = a.p0 + blockIdx.z;
   const int base = 2 * p * a.S;
   const int gi = base + a.S + ti, gj = base + tj;
   if (gi >= a.nb) return;
@@ -481,18 +482,86 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   const int n_outer = (nb + kOuter - 1) / kOuter;
   AuxStream aux(2 * n_outer);
   if (!aux.ok) return THANOS_ERR_HIP;
+
+  // The inverse of L (recursive doubling, see k_trinv_T / k_trinv_X) does not wait for the end
+  // of the factorisation: the merge of two halves at level S needs, for its first product
+  // L21 * Linv11, only the column blocks of the FIRST half (final once their panels are
+  // solved), and for its second product the inverse of the second half.  After every outer
+  // block the merges that have become possible are queued on a third stream, lowest level
+  // first and the first product before the second at each level (the order of their
+  // dependencies); they fill the compute units that the chain of diagonal blocks leaves idle.
+  // Regions written by different merges are disjoint, and none overlaps what the
+  // factorisation still writes.
+  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_T),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kXSmemBytes));
+  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_X),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kXSmemBytes));
+  AuxStream tri(n_outer + 1);
+  if (!tri.ok) return THANOS_ERR_HIP;
+  int tri_done = -1;  // blocks 0..tri_done have been handed to the inversion
+  int tri_batches = 0;
+  constexpr int tri_cap = 512;  // workgroups of one launch while the factorisation runs
+  auto trinv_upto = [&](int kdone) -> thanos_status {
+    // blocks <= kdone: diagonal inverse known, panel below solved (recorded on s by the caller)
+    THANOS_HIP_CHECK(hipEventRecord(tri.ev[tri_batches], s));
+    THANOS_HIP_CHECK(hipStreamWaitEvent(tri.stream, tri.ev[tri_batches], 0));
+    ++tri_batches;
+    for (int S = 1; S < nb; S *= 2) {
+      for (int second = 0; second < 2; ++second) {
+        int p_lo = -1, p_hi = -1;
+        for (int p = 0; 2 * p * S + S < nb; ++p) {
+          const int e = second ? std::min(2 * p * S + 2 * S, nb) - 1 : 2 * p * S + S - 1;
+          if (e > tri_done && e <= kdone) {
+            if (p_lo < 0) p_lo = p;
+            p_hi = p;
+          }
+        }
+        if (p_lo < 0) continue;
+        const int np = p_hi - p_lo + 1;
+        // rows of the second half that exist (the last pair of a level may be cut short)
+        const int rows = std::min(S, nb - (2 * p_hi * S + S));
+        const int rows_all = np > 1 ? S : rows;
+        // while the factorisation runs, a launch takes at most tri_cap workgroups (one round of
+        // the chip's workgroup slots), so that the short kernels of the chain are not queued
+        // behind thousands of long-running tiles
+        int cols = S;
+        if (kdone != nb - 1) cols = std::max(1, std::min(S, tri_cap / (rows_all * np)));
+        for (int c0 = 0; c0 < S; c0 += cols) {
+          TrinvArgs a{Ap, Linv, Tb, bp, nb, S, p_lo, c0};
+          dim3 grid((unsigned)std::min(cols, S - c0), (unsigned)rows_all, (unsigned)np);
+          if (second)
+            hipLaunchKernelGGL(k_trinv_X, grid, dim3(kXThreads), kXSmemBytes, tri.stream, a);
+          else
+            hipLaunchKernelGGL(k_trinv_T, grid, dim3(kXThreads), kXSmemBytes, tri.stream, a);
+          THANOS_LAUNCH_CHECK();
+        }
+      }
+    }
+    tri_done = kdone;
+    return THANOS_OK;
+  };
   int pending_join = -1;  // event index recorded on the aux stream after the last "rest"
   for (int k = 0; k < nb; ++k) {
     hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), kCholDiagSmem, s, Ap, Linv, bp, k, b, info);
     THANOS_LAUNCH_CHECK();
     const int64_t rem = bp - (int64_t)(k + 1) * NB;
-    if (rem <= 0) break;
+    if (rem <= 0) {
+      thanos_status st = trinv_upto(k);
+      if (st != THANOS_OK) return st;
+      break;
+    }
     float* panel = Ap + ((int64_t)(k + 1) * NB) * bp + (int64_t)k * NB;
     const float* dinv = Linv + ((int64_t)k * NB) * bp + (int64_t)k * NB;
     // L_ik = A_ik * Linv_kk^T  (in place, all rows below the diagonal block)
     thanos_status st = gemm_f32(s, false, false, rem, NB, NB, 1.f, panel, bp, dinv, bp, 0.f,
                                 panel, bp, false);
     if (st != THANOS_OK) return st;
+    if ((k + 1) % kOuter == 0) {
+      st = trinv_upto(k);
+      if (st != THANOS_OK) return st;
+    }
     const int ob = k / kOuter;
     const int ob_begin = ob * kOuter;
     const int ob_end = std::min(nb, ob_begin + kOuter);
@@ -537,20 +606,8 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   }
   if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
 
-  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_T),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kXSmemBytes));
-  THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_X),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kXSmemBytes));
-  for (int S = 1; S < nb; S *= 2) {
-    TrinvArgs a{Ap, Linv, Tb, bp, nb, S};
-    dim3 grid((unsigned)S, (unsigned)S, (unsigned)ceil_div(nb, 2 * S));
-    hipLaunchKernelGGL(k_trinv_T, grid, dim3(kXThreads), kXSmemBytes, s, a);
-    THANOS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_trinv_X, grid, dim3(kXThreads), kXSmemBytes, s, a);
-    THANOS_LAUNCH_CHECK();
-  }
+  THANOS_HIP_CHECK(hipEventRecord(tri.ev[n_outer], tri.stream));
+  THANOS_HIP_CHECK(hipStreamWaitEvent(s, tri.ev[n_outer], 0));
 
   hipLaunchKernelGGL(k_reverse_out, dim3((unsigned)ceil_div(b, 256), (unsigned)b), dim3(256), 0, s,
                      Linv, bp, U, b);
