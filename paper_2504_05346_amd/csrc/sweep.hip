@@ -23,6 +23,13 @@ namespace thanos {
     __builtin_amdgcn_wave_barrier();                       \
   } while (0)
 
+// The value of lane (l & 31) for every lane l: the lower half of the wavefront broadcast to the
+// upper half (one v_permlane32_swap, no trip through LDS).
+__device__ __forceinline__ float lower_half(float v) {
+  const unsigned int u = __float_as_uint(v);
+  return __uint_as_float(__builtin_amdgcn_permlane32_swap(u, u, false, false)[0]);
+}
+
 // ------------------------------------------------------------------------------------------
 // small helpers
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
@@ -857,7 +864,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
         const int k1 = 8 * (t >> 2) + (t & 3), k2 = k1 + 4;
         if (p > 0 || k1 < 32 - pad) {  // a padding row paired with a real one is a no-op pivot
           const float v = T[p][p][t];   // lower half: row k1 of the reduced tile, upper half: row k2
-          const float x = __shfl(v, lo, 64);
+          const float x = lower_half(v);
           const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k1));
           const float c12 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k2));
           const float d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32 + k2));
@@ -876,16 +883,16 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
           const float mh = hi ? m : 0.f;
           const float rh = hi ? -r2 : -r1;
           const float yh = hi ? y2 : y1;
-          // u1 (lower half) and u2 = row k2 after the elimination of k1 (upper half); columns
-          // eliminated earlier are zero, and so is column k1 of u2
-          const bool live = pl >= 2 * t && !(hi && lo == k1);
-          const float bop = live ? fmaf(-mh, x, v) : 0.f;
+          // u1 (lower half) and u2 = row k2 after the elimination of k1 (upper half).  Columns
+          // eliminated earlier hold rounding residue instead of zero; it is not masked, because
+          // a product with it only ever lands in eliminated rows and columns of the tiles and in
+          // right-hand-side rows that have already been read.
+          const float bop = fmaf(-mh, x, v);
           const float aop = bop * rh;
           T[p][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(aop, bop, T[p][p], 0, 0, 0);
           // column 2t + hi of L~ within the tile: rows at later positions
           (pl > 2 * t + hi ? rowp[p] + 32 * p + hi : junk)[2 * t] = -aop;
-          const float a2 = (lo == (hi ? k2 : k1)) ? 0.f : aop;  // the pivot rows themselves stay
-          uv[p] = fmaf(a2, yh, uv[p]);
+          uv[p] = fmaf(aop, yh, uv[p]);
           if ((lane >> 1) == (((32 * p + 2 * t) & 63) >> 1))
             zz[(32 * p + 2 * t) >> 6] = (lane & 1) ? y2 * r2 : y1 * r1;
           float e2[NTR], be[NTR];
@@ -894,7 +901,7 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
             if (ti < nt) {
               // R_hat[32 ti + lo][32 p + k1] (lower half) and [..][32 p + k2] (upper half)
               const float ev = T[ti][p][t];
-              const float xe = __shfl(ev, lo, 64);
+              const float xe = lower_half(ev);
               e2[ti] = fmaf(-mh, xe, ev);
               be[ti] = rh * e2[ti];
               T[ti][p] = __builtin_amdgcn_mfma_f32_32x32x2f32(bop, be[ti], T[ti][p], 0, 0, 0);
@@ -1022,7 +1029,7 @@ __device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int l
   for (int t = 0; t < 16; ++t) {              // pair t: rows k1 and k2 = k1 + 4, both in D[t]
     const int k1 = 8 * (t >> 2) + (t & 3), k2 = k1 + 4;
     const float v = D[t];                     // lower half: D[k1][lo], upper half: D[k2][lo]
-    const float x = __shfl(v, lo, 64);        // D[k1][lo] in both halves
+    const float x = lower_half(v);        // D[k1][lo] in both halves
     const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k1));
     const float c12 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k2));
     const float d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32 + k2));
@@ -1043,7 +1050,7 @@ __device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int l
     // the same row operations on T~: row k1 as it is, row k2 after the operation of k1; the
     // pivot rows themselves stay
     const float ev = E[t];
-    const float xe = __shfl(ev, lo, 64);
+    const float xe = lower_half(ev);
     const float be = fmaf(-mh, xe, ev);
     const float a2 = (lo == (hi ? k2 : k1)) ? 0.f : aop;
     E = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, be, E, 0, 0, 0);
