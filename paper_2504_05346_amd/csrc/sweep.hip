@@ -685,7 +685,9 @@ struct SolveMfmaSmem {
   float dummy[128];
 };
 
-template <int SEL, int WPB, int NTR>
+// FULL: the host knows that every row has either no unknown or exactly 32 NTR (n:m on a whole
+// block): the padding logic folds away.
+template <int SEL, int WPB, int NTR, bool FULL = false>
 __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   constexpr int CPL = 2;  // block width <= 128
   constexpr int NZ = (NTR + 1) / 2;  // registers holding y / d: rows 64 z + lane
@@ -781,7 +783,8 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
     if (lane == 0) a.row_cnt[i] = s;  // summed at the start of the next block
   }
   float* lam_g = a.Lam + i * a.ldl;
-  if (s == 0 || s > 32 * NTR) {  // s > 32 NTR cannot happen for a launch chosen by the host
+  // s > 32 NTR (or, if FULL, anything but 32 NTR) cannot happen for a launch chosen by the host
+  if (s == 0 || s > 32 * NTR || (FULL && s != 32 * NTR)) {
 #pragma unroll
     for (int r = 0; r < CPL; ++r) {
       const int col = lane + 64 * r;
@@ -796,10 +799,12 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   //      unknown m - pad.  A pivot costs one MFMA per live tile, most in the first tile row
   //      (NTR (NTR + 1) / 2 of them): with the short tile row in front, a system of 66 unknowns
   //      costs 2 * 6 + 32 * 3 + 32 MFMAs instead of 32 * 6 + 32 * 3 + 2. ----
-  const int nt = (s + 31) >> 5;
-  const int pad = 32 * nt - s;
-  auto valid = [&](int m) { return m < 32 - pad || (m >= 32 && m - pad < s); };
-  auto unk = [&](int m) { return min(m < 32 ? m : m - pad, s - 1); };  // clamped: always a valid index
+  const int nt = FULL ? NTR : (s + 31) >> 5;
+  const int pad = FULL ? 0 : 32 * nt - s;
+  auto valid = [&](int m) { return FULL || m < 32 - pad || (m >= 32 && m - pad < s); };
+  auto unk = [&](int m) {  // clamped: always a valid index
+    return FULL ? m : min(m < 32 ? m : m - pad, s - 1);
+  };
 
   // ---- gather R_hat = G[q, q] into the tiles (all loads unconditional from clamped, valid
   //      indices, masked afterwards); right-hand side distributed by row ----
@@ -1617,6 +1622,13 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
     const size_t smem = kWpb * sizeof(SolveMfmaSmem<2>);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfma<SEL, kWpb, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (SEL == SEL_NM && a.bw * a.n == 64 * a.m && a.bw % a.m == 0) {  // 64 unknowns in every row
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_mfma<SEL, kWpb, 2, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb, 2, true>), dim3((unsigned)ceil_div(a.c, kWpb)),
+                         dim3(64 * kWpb), smem, s, a);
+      return;
+    }
     hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb, 2>), dim3((unsigned)ceil_div(a.c, kWpb)),
                        dim3(64 * kWpb), smem, s, a);
   } else if (a.bw <= 128) {
