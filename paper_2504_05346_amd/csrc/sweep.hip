@@ -125,30 +125,137 @@ __global__ __launch_bounds__(kXThreads, 4) void k_block_rows(BlockRowsArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Unstructured selection: exact r-th smallest metric over the residual W[:, j1:b] by a 3-pass
-// radix select on the fp32 bit pattern (11 + 11 + 10 bits), all state on the device.
+// Unstructured selection: exact r-th smallest metric over the residual W[:, j1:b] by a radix
+// select on the fp32 bit pattern (11 + 11 + 10 bits), all state on the device.
+//
+// The threshold of a block is predicted from the previous block's: the update that writes the
+// new weights also histograms a window of 2048 x 16 keys around the previous tau (and counts
+// what lies below it).  If the wanted rank falls inside the window, 28 bits of the key are
+// resolved, the first two radix passes leave at once and the last one resolves 4 bits.
+//
+// Launches per block: k_sel_start, k_sel_hist<0>, <1>, <2>, k_tie_rows, k_tie_scan.  There is no
+// kernel that only scans a histogram: every workgroup of the NEXT pass scans the (small)
+// histogram of the previous pass for itself, and workgroup 0 also writes the result to the
+// state for later kernels.  Fields are written by one pass and read by later ones only, so the
+// redundant scans race with nothing.
 struct SelState {
   long long r_rem;      // weights still to remove (before the current block)
-  long long rank;       // rank still to resolve inside the current prefix
   long long need_eq;    // how many keys equal to tau are removed (ties, in (row, col) order)
   int ties_all;         // every key equal to tau is removed: no ranking of ties (need_eq = 2^62)
   int deferred;         // 1: some row of the block was left to the second solver launch
-  unsigned int prefix;  // resolved high bits
   unsigned int tau;     // r-th smallest key
   int none;             // 1: nothing left to remove
-  // prediction from the previous block: the threshold moves little from block to block (a few
-  // thousand key values at the headline shape), so one pass that histograms a window of
-  // 2048 x 16 keys around the previous tau (and counts what lies below it) usually replaces the
-  // first two radix passes and leaves 4 bits to the last one
-  unsigned long long below;  // keys below the window
-  unsigned int win_lo;       // first 28-bit prefix (key >> 4) of the window
-  int pred_try;              // 1: a previous tau exists
-  int pred_ok;               // 1: the rank fell inside the window, prefix holds 28 bits
-  int shift;                 // low bits left to the last pass: 10, or 4 after a window hit
+  unsigned int win_lo;  // first 28-bit prefix (key >> 4) of the window of the NEXT block
+  int pred_try;         // 1: a window was counted for this block
+  int pred_ok;          // 1: the rank fell inside the window: prefix0 holds 28 bits
+  int shift;            // low bits resolved by the last pass: 10, or 4 after a window hit
+  // rank still to resolve and resolved high bits after k_sel_start (0), after the scan of
+  // pass 0 (1), and going into the last pass (2)
+  long long rank0, rank1, rank2;
+  unsigned int prefix0, prefix1, prefix2;
 };
 
 __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
   return __float_as_uint(fabsf(w) * sx);
+}
+
+// Workgroup of 256 threads: the bin of hist[0 .. nbins) (nbins = 16, 1024 or 2048) that holds
+// the rank-th smallest key, the number of keys in the bins before it and inside it.  bin = -1
+// if rank is not in 1 .. total.
+struct BinSel {
+  int bin;
+  unsigned int count;
+  long long before;
+};
+__device__ __forceinline__ BinSel block_select_bin(const unsigned int* __restrict__ hist,
+                                                   int nbins, long long rank) {
+  __shared__ long long wtot[4];
+  __shared__ BinSel res;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = nbins >= 256 ? nbins >> 8 : 1;
+  unsigned int loc[8];
+  long long s = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int idx = tid * per + e;
+    loc[e] = (e < per && idx < nbins) ? hist[idx] : 0u;
+    s += loc[e];
+  }
+  long long incl = s;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long t = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += t;
+  }
+  if (lane == 63) wtot[wave] = incl;
+  if (tid == 0) res.bin = -1;
+  __syncthreads();
+  long long before = incl - s;
+  for (int v = 0; v < wave; ++v) before += wtot[v];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (rank > 0 && before < rank && rank <= before + loc[e]) {
+      res.bin = tid * per + e;
+      res.count = loc[e];
+      res.before = before;
+    }
+    before += loc[e];
+  }
+  __syncthreads();
+  const BinSel r = res;
+  __syncthreads();  // res and wtot are free for the next call
+  return r;
+}
+
+// Start of a block (one workgroup): r <- r - ||M||_F^2 of the previous block (Alg. 1;
+// row_cnt[i] = weights the previous block removed from row i: one array entry per row instead of
+// thousands of atomics on one counter), then the scan of the window histogram that the previous
+// block's update filled (hist_w, plus one count per workgroup of the keys below the window).
+// The histograms of the three radix passes (3 x 2048 bins behind hist_w) are cleared here.
+__global__ __launch_bounds__(256) void k_sel_start(SelState* __restrict__ st, int first,
+                                                   const int* __restrict__ row_cnt, int64_t c,
+                                                   unsigned int* __restrict__ hist_w,
+                                                   const unsigned int* __restrict__ below_part,
+                                                   int n_part) {
+  __shared__ long long part[256];
+  const int tid = threadIdx.x;
+  long long sum = 0, bsum = 0;
+  if (!first) {
+    for (int64_t i = tid; i < c; i += 256) sum += row_cnt[i];
+    for (int e = tid; e < n_part; e += 256) bsum += below_part[e];
+  }
+  const long long r_old = st->r_rem;
+  const bool pred_try = !first && st->pred_try != 0;
+  const unsigned int win_lo = st->win_lo;
+  part[tid] = sum;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (tid < off) part[tid] += part[tid + off];
+    __syncthreads();
+  }
+  const long long r_rem = r_old - part[0];
+  __syncthreads();
+  part[tid] = bsum;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (tid < off) part[tid] += part[tid + off];
+    __syncthreads();
+  }
+  const long long below = part[0];
+  const bool none = r_rem <= 0;
+  BinSel r;
+  r.bin = -1;
+  if (!none && pred_try) r = block_select_bin(hist_w, 2048, r_rem - below);
+  if (tid == 0) {
+    st->r_rem = r_rem;
+    st->none = none ? 1 : 0;
+    st->deferred = 0;
+    const bool hit = r.bin >= 0;
+    st->pred_ok = hit ? 1 : 0;
+    st->prefix0 = hit ? win_lo + (unsigned int)r.bin : 0u;
+    st->rank0 = hit ? r_rem - below - r.before : r_rem;
+  }
+  for (int e = tid; e < 4 * 2048; e += 256) hist_w[e] = 0u;
 }
 
 // One wavefront per row; lanes stride over the residual columns (16 bytes per lane when the
@@ -171,20 +278,50 @@ __device__ __forceinline__ void sel_count(unsigned int* h, unsigned int key, uns
   }
 }
 
+// hist_in: histogram of the previous pass (scanned by every workgroup), hist_out: this pass's.
 template <int PASS>
 __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, int64_t c, int64_t b,
                                                   int64_t j1, const float* __restrict__ sx,
-                                                  const SelState* __restrict__ st,
-                                                  unsigned int* __restrict__ hist,
+                                                  SelState* __restrict__ st,
+                                                  const unsigned int* __restrict__ hist_in,
+                                                  unsigned int* __restrict__ hist_out,
                                                   int* __restrict__ row_cand, int vec) {
   __shared__ unsigned int h[2048];
   if (st->none) return;
-  if (PASS < 2 && st->pred_ok) return;  // the window pass already resolved 22 bits
+  const bool pred_ok = st->pred_ok != 0;
+  if (PASS < 2 && pred_ok) return;  // the window already resolved 28 bits
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned int prefix = 0u;
+  int shift = 0;
+  if (PASS == 1) {
+    const long long rank0 = st->rank0;
+    const BinSel r = block_select_bin(hist_in, 2048, rank0);
+    prefix = (unsigned int)r.bin;
+    if (blockIdx.x == 0 && tid == 0) {
+      st->prefix1 = prefix;
+      st->rank1 = rank0 - r.before;
+    }
+  } else if (PASS == 2) {
+    long long rank2;
+    if (pred_ok) {
+      prefix = st->prefix0;
+      rank2 = st->rank0;
+      shift = 4;
+    } else {
+      const long long rank1 = st->rank1;
+      const BinSel r = block_select_bin(hist_in, 2048, rank1);
+      prefix = (st->prefix1 << 11) | (unsigned int)r.bin;
+      rank2 = rank1 - r.before;
+      shift = 10;
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+      st->prefix2 = prefix;
+      st->rank2 = rank2;
+      st->shift = shift;
+    }
+  }
   for (int e = tid; e < 2048; e += 256) h[e] = 0u;
   __syncthreads();
-  const unsigned int prefix = st->prefix;
-  const int shift = st->shift;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave;
   if (i < c) {
     const float* row = W + i * b;
@@ -213,178 +350,46 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
   }
   __syncthreads();
   for (int e = tid; e < 2048; e += 256)
-    if (h[e]) atomicAdd(&hist[e], h[e]);
+    if (h[e]) atomicAdd(&hist_out[e], h[e]);
 }
 
-// Start of a block: r <- r - ||M||_F^2 of the previous block (Alg. 1), reset the search.
-// (row_cnt[i] = weights the previous block removed from row i; one array entry per row instead
-// of thousands of atomics on one counter.)
-__global__ __launch_bounds__(256) void k_sel_begin(SelState* __restrict__ st, int first,
-                                                   const int* __restrict__ row_cnt, int64_t c) {
-  __shared__ long long part[256];
-  const int tid = threadIdx.x;
-  long long sum = 0;
-  if (!first)
-    for (int64_t i = tid; i < c; i += 256) sum += row_cnt[i];
-  part[tid] = sum;
-  __syncthreads();
-  for (int off = 128; off > 0; off >>= 1) {
-    if (tid < off) part[tid] += part[tid + off];
-    __syncthreads();
-  }
-  if (tid != 0) return;
-  st->r_rem -= part[0];
-  st->rank = st->r_rem;
-  st->prefix = 0u;
-  st->none = (st->r_rem <= 0) ? 1 : 0;
-  const unsigned int p28 = st->tau >> 4;
-  st->pred_try = (!first && st->tau != 0u) ? 1 : 0;
-  st->win_lo = p28 > 1024u ? p28 - 1024u : 0u;
-  st->below = 0ull;
-  st->pred_ok = 0;
-  st->shift = 10;
-  st->deferred = 0;
-}
-
-// Window pass: bin = (key >> 4) - win_lo for the 2048 prefixes of the window, keys below the
-// window are counted, keys above it ignored.  It has no kernel of its own: k_update counts the
-// new weights of the columns right of the block while it writes them (one pass over the residual
-// less per block), after k_sel_begin has set the window for the next block.
-// If the rank lies inside the window: 28 bits of the key are resolved, the first two radix
-// passes are skipped and the last one resolves 4 bits.  Otherwise nothing is changed and all
-// three run.
-__global__ __launch_bounds__(256) void k_sel_scan_win(SelState* __restrict__ st,
-                                                      unsigned int* __restrict__ hist,
-                                                      const unsigned int* __restrict__ below_part,
-                                                      int n_part) {
-  __shared__ long long part[256];
-  __shared__ int sel_bin;
-  __shared__ long long sel_before;
-  const int tid = threadIdx.x;
-  if (st->none || !st->pred_try) return;
-  long long bsum = 0;
-  for (int e = tid; e < n_part; e += 256) bsum += below_part[e];
-  part[tid] = bsum;
-  __syncthreads();
-  for (int off = 128; off > 0; off >>= 1) {
-    if (tid < off) part[tid] += part[tid + off];
-    __syncthreads();
-  }
-  const long long below = part[0];
-  __syncthreads();
-  if (tid == 0) st->below = (unsigned long long)below;
-  const long long rank = st->rank - below;  // rank inside the window
-  unsigned int loc[8];
-  long long s = 0;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    loc[e] = hist[tid * 8 + e];
-    s += loc[e];
-  }
-  part[tid] = s;
-  if (tid == 0) sel_bin = -1;
-  __syncthreads();
-  if (tid == 0) {
-    long long run = 0;
-    for (int t = 0; t < 256; ++t) {
-      const long long v = part[t];
-      part[t] = run;
-      run += v;
-    }
-  }
-  __syncthreads();
-  long long before = part[tid];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    if (rank > 0 && before < rank && rank <= before + loc[e]) {
-      sel_bin = tid * 8 + e;
-      sel_before = before;
-    }
-    before += loc[e];
-  }
-  __syncthreads();
-  if (tid == 0 && sel_bin >= 0) {
-    st->prefix = st->win_lo + (unsigned int)sel_bin;
-    st->rank = rank - sel_before;
-    st->pred_ok = 1;
-    st->shift = 4;
-  }
-  for (int e = tid; e < 2048; e += 256) hist[e] = 0u;
-}
-
-template <int PASS>
-__global__ __launch_bounds__(256) void k_sel_scan(SelState* __restrict__ st,
-                                                  unsigned int* __restrict__ hist) {
-  __shared__ long long part[256];
-  __shared__ int sel_bin;
-  __shared__ long long sel_before;
-  __shared__ unsigned int sel_count;
-  const int tid = threadIdx.x;
-  if (st->none) return;  // the histogram passes did not run either
-  if (PASS < 2 && st->pred_ok) return;
-  const long long rank = st->rank;
-  unsigned int loc[8];
-  long long s = 0;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    loc[e] = hist[tid * 8 + e];
-    s += loc[e];
-  }
-  part[tid] = s;
-  __syncthreads();
-  if (tid == 0) {
-    long long run = 0;
-    for (int t = 0; t < 256; ++t) {
-      const long long v = part[t];
-      part[t] = run;
-      run += v;
-    }
-  }
-  __syncthreads();
-  long long before = part[tid];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    if (before < rank && rank <= before + loc[e]) {
-      sel_bin = tid * 8 + e;
-      sel_before = before;
-      sel_count = loc[e];
-    }
-    before += loc[e];
-  }
-  __syncthreads();
-  if (tid == 0) {
-    const int bits = (PASS == 2) ? st->shift : 11;
-    st->prefix = (st->prefix << bits) | (unsigned int)sel_bin;
-    st->rank = rank - sel_before;
-    if (PASS == 2) {
-      // The last pass resolves the key completely, so the chosen bin counts the keys equal to
-      // tau.  If all of them are removed (the usual case: one key at the threshold) their order
-      // does not matter and the two tie kernels have nothing to do.
-      const bool all = st->rank == (long long)sel_count;
-      st->tau = st->prefix;
-      st->need_eq = all ? (1ll << 62) : st->rank;
-      st->ties_all = all ? 1 : 0;
-    }
-  }
-  for (int e = tid; e < 2048; e += 256) hist[e] = 0u;
-}
-
-// Ties: rows that hold candidates (keys sharing the bits of tau resolved before the last pass) count their keys equal to
-// tau over the residual row; other rows have none.
+// Scan of the last pass (every workgroup; workgroup 0 writes tau, the tie budget and the window
+// of the next block), then the ties: rows that hold candidates (keys sharing the bits of tau
+// resolved before the last pass) count their keys equal to tau over the residual row; other rows
+// have none.  The last pass resolves the key completely, so the chosen bin counts the keys
+// equal to tau: if all of them are removed (the usual case: one key at the threshold) their
+// order does not matter and nothing is counted.
 __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, int64_t c, int64_t b,
                                                   int64_t j1, const float* __restrict__ sx,
-                                                  const SelState* __restrict__ st,
+                                                  SelState* __restrict__ st,
+                                                  const unsigned int* __restrict__ hist_in,
                                                   const int* __restrict__ row_cand,
                                                   int* __restrict__ row_eq, int vec) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave;
-  if (i >= c) return;
-  if (st->ties_all) return;  // row_eq is not read: every tie passes the test against need_eq
-  if (st->none || row_cand[i] == 0) {
+  if (st->none) {  // uniform
+    if (i < c && lane == 0) row_eq[i] = 0;
+    return;
+  }
+  const int shift = st->shift;
+  const long long rank2 = st->rank2;
+  const BinSel r = block_select_bin(hist_in, 1 << shift, rank2);
+  const unsigned int tau = (st->prefix2 << shift) | (unsigned int)r.bin;
+  const long long rank_eq = rank2 - r.before;  // keys equal to tau that are removed
+  const bool all = rank_eq == (long long)r.count;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    st->tau = tau;
+    st->need_eq = all ? (1ll << 62) : rank_eq;
+    st->ties_all = all ? 1 : 0;
+    const unsigned int p28 = tau >> 4;
+    st->pred_try = tau != 0u ? 1 : 0;
+    st->win_lo = p28 > 1024u ? p28 - 1024u : 0u;
+  }
+  if (all || i >= c) return;  // row_eq is not read: every tie passes the test against need_eq
+  if (row_cand[i] == 0) {
     if (lane == 0) row_eq[i] = 0;
     return;
   }
-  const unsigned int tau = st->tau;
   const float* row = W + i * b;
   int n = 0;
   if (vec) {
@@ -1372,7 +1377,7 @@ struct UpdateArgs {
   int vec_w;            // W 8-byte and mask 2-byte aligned, b and col0 even: row pass in pairs
   // Unstructured mode: while the new weights are at hand, the columns right of the block are
   // histogrammed for the NEXT block's selection (window around the current threshold, see
-  // k_sel_begin / k_sel_scan_win); hist == nullptr switches this off.
+  // k_tie_rows / k_sel_start); hist == nullptr switches this off.
   unsigned int* hist;         // 2048 bins, global
   unsigned int* below_part;   // keys below the window, one count per workgroup
   const SelState* st;
@@ -1455,7 +1460,7 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
     }
   }
   if (a.hist == nullptr) return;
-  // one partial count of the keys below the window per workgroup (summed by k_sel_scan_win:
+  // one partial count of the keys below the window per workgroup (summed by k_sel_start:
   // thousands of atomics on one address would cost more than the pass), window bins by atomics
   for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
   if (lane == 0) nb_wave[wave] = nb;
@@ -1563,7 +1568,7 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers) {
   n += align_up((size_t)b * 4, 256);            // sx
   n += align_up((size_t)c * B * kSuper * 4 * 2, 256);  // Lam, two super-block buffers
   n += align_up((size_t)b * b * 4, 256);        // P
-  n += align_up(2048 * 4, 256);                 // hist
+  n += align_up(4 * 2048 * 4, 256);             // hist: window + three passes
   n += align_up(sizeof(SelState), 256);         // state
   n += 2 * align_up((size_t)c * 4, 256);        // row_cand, row_eq
   n += align_up((size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4, 256);  // below_part
@@ -1582,7 +1587,7 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers) {
   w.sx = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
   w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * kSuper * 4 * 2));
   w.P = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
-  w.hist = reinterpret_cast<unsigned int*>(carve(p, 2048 * 4));
+  w.hist = reinterpret_cast<unsigned int*>(carve(p, 4 * 2048 * 4));  // window + three passes
   w.st = reinterpret_cast<SelState*>(carve(p, sizeof(SelState)));
   w.row_cand = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
   w.row_eq = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
@@ -1601,18 +1606,17 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers) {
 
 __global__ void k_init_state(SelState* st, long long r) {
   st->r_rem = r;
-  st->rank = 0;
   st->need_eq = 0;
   st->ties_all = 0;
   st->deferred = 0;
-  st->prefix = 0u;
   st->tau = 0u;
   st->none = (r <= 0) ? 1 : 0;
-  st->below = 0ull;
   st->win_lo = 0u;
   st->pred_try = 0;
   st->pred_ok = 0;
   st->shift = 10;
+  st->rank0 = st->rank1 = st->rank2 = 0;
+  st->prefix0 = st->prefix1 = st->prefix2 = 0u;
 }
 
 template <int SEL>
@@ -1723,7 +1727,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
 
   const bool unstructured = (o->mode == THANOS_UNSTRUCTURED) && o->mask_in == nullptr;
   if (unstructured) {
-    hipLaunchKernelGGL(k_fill_u32, dim3(8), dim3(256), 0, s, w.hist, (int64_t)2048, 0u);
+    hipLaunchKernelGGL(k_fill_u32, dim3(32), dim3(256), 0, s, w.hist, (int64_t)4 * 2048, 0u);
     hipLaunchKernelGGL(k_init_state, dim3(1), dim3(1), 0, s, w.st, r_total);
     THANOS_LAUNCH_CHECK();
   }
@@ -1752,25 +1756,21 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       // 16-byte loads need W + i*b + j1 and sx + j1 aligned (W, sx come 256-byte aligned)
       const int sel_vec = (b % 4 == 0 && j1 % 4 == 0 &&
                            reinterpret_cast<uintptr_t>(W) % 16 == 0) ? 1 : 0;
-      // k_sel_begin of this block ran before the previous block's update, which then counted
-      // the window around the previous threshold while it wrote the new weights
-      if (j1 == 0) {
-        hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(256), 0, s, w.st, 1, w.row_cand, c);
-      } else {
-        hipLaunchKernelGGL(k_sel_scan_win, dim3(1), dim3(256), 0, s, w.st, w.hist, w.below_part,
-                           win_parts);
-      }
+      // the previous block's update counted the window around its threshold while it wrote
+      // the new weights
+      unsigned int* hist_a = w.hist + 2048;
+      unsigned int* hist_b = w.hist + 2 * 2048;
+      unsigned int* hist_c = w.hist + 3 * 2048;
+      hipLaunchKernelGGL(k_sel_start, dim3(1), dim3(256), 0, s, w.st, j1 == 0 ? 1 : 0, w.row_cand, c,
+                         w.hist, w.below_part, win_parts);
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.hist, w.row_cand, sel_vec);
-      hipLaunchKernelGGL(k_sel_scan<0>, dim3(1), dim3(256), 0, s, w.st, w.hist);
+                         nullptr, hist_a, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_sel_hist<1>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.hist, w.row_cand, sel_vec);
-      hipLaunchKernelGGL(k_sel_scan<1>, dim3(1), dim3(256), 0, s, w.st, w.hist);
+                         hist_a, hist_b, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_sel_hist<2>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.hist, w.row_cand, sel_vec);
-      hipLaunchKernelGGL(k_sel_scan<2>, dim3(1), dim3(256), 0, s, w.st, w.hist);
+                         hist_b, hist_c, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         w.row_cand, w.row_eq, sel_vec);
+                         hist_c, w.row_cand, w.row_eq, sel_vec);
       hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c, w.st);
       THANOS_LAUNCH_CHECK();
     }
@@ -1809,10 +1809,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     {  // this block's update, up to the end of its super-block
       dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
       const bool feed = unstructured && j1 + bw < b;  // a next block exists: count its window
-      if (feed) {
-        hipLaunchKernelGGL(k_sel_begin, dim3(1), dim3(256), 0, s, w.st, 0, w.row_cand, c);
-        win_parts = (int)(grid.x * grid.y);
-      }
+      if (feed) win_parts = (int)(grid.x * grid.y);
       UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
                     (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w,
                     feed ? w.hist : nullptr, w.below_part, w.st, w.sx};
