@@ -1382,6 +1382,7 @@ struct UpdateArgs {
   unsigned int* below_part;   // keys below the window, one count per workgroup
   const SelState* st;
   const float* sx;
+  int gx, gy;                 // tile grid (set by launch_update)
 };
 
 constexpr size_t kUpdSmemBytes = kXSmemBytes + 2048 * sizeof(unsigned int) + 16 * sizeof(unsigned int);
@@ -1390,8 +1391,23 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   unsigned int* hw = reinterpret_cast<unsigned int*>(sm + kXSmemBytes);  // window histogram
   unsigned int* nb_wave = hw + 2048;
-  const int64_t m0 = (int64_t)blockIdx.y * kTM;
-  const int64_t n0 = a.col0 + (int64_t)blockIdx.x * kTN;
+  // Tile of this workgroup.  Consecutive workgroup ids go to the eight XCDs in turn, each with
+  // an L2 of its own: XCD x takes the row tiles x*rp .. x*rp + rp - 1 and walks them column by
+  // column, so that it reads one eighth of the multipliers and every tile of P_k once.
+  // (With fewer than 16 row tiles the XCDs would not get equal shares: plain order.)
+  int bx, by;
+  if (a.gy >= 16) {
+    const int rp = (a.gy + 7) >> 3;
+    const int slot = (int)blockIdx.x >> 3;
+    bx = slot / rp;
+    by = ((int)blockIdx.x & 7) * rp + (slot - bx * rp);
+    if (by >= a.gy) return;
+  } else {
+    by = (int)blockIdx.x / a.gx;
+    bx = (int)blockIdx.x - by * a.gx;
+  }
+  const int64_t m0 = (int64_t)by * kTM;
+  const int64_t n0 = a.col0 + (int64_t)bx * kTN;
   const int m_ext = (int)min((int64_t)kTM, a.c - m0);
   const int n_ext = (int)min((int64_t)kTN, a.col_end - n0);
   const float* A = a.Lam + m0 * a.ldl;          // (m,k) at A[m*ldl + k]
@@ -1468,7 +1484,7 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   if (threadIdx.x == 0) {
     unsigned int t = 0;
     for (int v = 0; v < kXThreads / 64; ++v) t += nb_wave[v];
-    a.below_part[blockIdx.y * gridDim.x + blockIdx.x] = t;
+    a.below_part[by * a.gx + bx] = t;
   }
   if (win)
     for (int e = threadIdx.x; e < 2048; e += kXThreads)
@@ -1562,6 +1578,14 @@ static char* carve(char*& p, size_t bytes) {
 // end of the super-block, and everything right of it gets one update per super-block with a
 // kSuper times longer reduction (the multipliers of all its blocks are kept, c x kSuper*B).
 constexpr int kSuper = 8;
+
+static void launch_update(hipStream_t s, UpdateArgs ua, dim3 tiles) {
+  ua.gx = (int)tiles.x;
+  ua.gy = (int)tiles.y;
+  const unsigned rp = (tiles.y + 7) / 8;
+  const unsigned n = tiles.y >= 16 ? 8 * rp * tiles.x : tiles.x * tiles.y;
+  hipLaunchKernelGGL(k_update, dim3(n), dim3(kXThreads), kUpdSmemBytes, s, ua);
+}
 
 size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers) {
   size_t n = 0;
@@ -1813,7 +1837,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
                     (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w,
                     feed ? w.hist : nullptr, w.below_part, w.st, w.sx};
-      hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kUpdSmemBytes, s, ua);
+      launch_update(s, ua, grid);
       THANOS_LAUNCH_CHECK();
     }
     if (super > 1 && j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block
@@ -1826,7 +1850,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                       (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
                       nullptr};
         dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
-        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kUpdSmemBytes, aux.stream, ua);
+        launch_update(aux.stream, ua, grid);
         THANOS_LAUNCH_CHECK();
       }
       if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
@@ -1835,7 +1859,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                       (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
                       nullptr};
         dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
-        hipLaunchKernelGGL(k_update, grid, dim3(kXThreads), kUpdSmemBytes, s, ua);
+        launch_update(s, ua, grid);
         THANOS_LAUNCH_CHECK();
       }
       if (next_end < b) {
