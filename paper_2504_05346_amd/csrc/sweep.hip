@@ -159,7 +159,7 @@ __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
   return __float_as_uint(fabsf(w) * sx);
 }
 
-// Workgroup of 256 threads: the bin of hist[0 .. nbins) (nbins = 16, 1024 or 2048) that holds
+// Workgroup of NT threads: the bin of hist[0 .. nbins) (nbins = 16, 1024 or 2048) that holds
 // the rank-th smallest key, the number of keys in the bins before it and inside it.  bin = -1
 // if rank is not in 1 .. total.
 struct BinSel {
@@ -167,12 +167,13 @@ struct BinSel {
   unsigned int count;
   long long before;
 };
+template <int NT>
 __device__ __forceinline__ BinSel block_select_bin(const unsigned int* __restrict__ hist,
                                                    int nbins, long long rank) {
-  __shared__ long long wtot[4];
+  __shared__ long long wtot[NT / 64];
   __shared__ BinSel res;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int per = nbins >= 256 ? nbins >> 8 : 1;
+  const int per = nbins >= NT ? nbins / NT : 1;  // at most 8
   unsigned int loc[8];
   long long s = 0;
 #pragma unroll
@@ -207,45 +208,44 @@ __device__ __forceinline__ BinSel block_select_bin(const unsigned int* __restric
   return r;
 }
 
+// Sum of one value per thread over a workgroup of NT threads (all threads get it).
+template <int NT>
+__device__ __forceinline__ long long block_sum(long long v) {
+  __shared__ long long wsum[NT / 64];
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  long long t = 0;
+  for (int w = 0; w < NT / 64; ++w) t += wsum[w];
+  __syncthreads();
+  return t;
+}
+
 // Start of a block (one workgroup): r <- r - ||M||_F^2 of the previous block (Alg. 1;
 // row_cnt[i] = weights the previous block removed from row i: one array entry per row instead of
 // thousands of atomics on one counter), then the scan of the window histogram that the previous
 // block's update filled (hist_w, plus one count per workgroup of the keys below the window).
 // The histograms of the three radix passes (3 x 2048 bins behind hist_w) are cleared here.
-__global__ __launch_bounds__(256) void k_sel_start(SelState* __restrict__ st, int first,
-                                                   const int* __restrict__ row_cnt, int64_t c,
-                                                   unsigned int* __restrict__ hist_w,
-                                                   const unsigned int* __restrict__ below_part,
-                                                   int n_part) {
-  __shared__ long long part[256];
+__global__ __launch_bounds__(1024) void k_sel_start(SelState* __restrict__ st, int first,
+                                                    const int* __restrict__ row_cnt, int64_t c,
+                                                    unsigned int* __restrict__ hist_w,
+                                                    const unsigned int* __restrict__ below_part,
+                                                    int n_part) {
   const int tid = threadIdx.x;
   long long sum = 0, bsum = 0;
   if (!first) {
-    for (int64_t i = tid; i < c; i += 256) sum += row_cnt[i];
-    for (int e = tid; e < n_part; e += 256) bsum += below_part[e];
+    for (int64_t i = tid; i < c; i += 1024) sum += row_cnt[i];
+    for (int e = tid; e < n_part; e += 1024) bsum += below_part[e];
   }
   const long long r_old = st->r_rem;
   const bool pred_try = !first && st->pred_try != 0;
   const unsigned int win_lo = st->win_lo;
-  part[tid] = sum;
-  __syncthreads();
-  for (int off = 128; off > 0; off >>= 1) {
-    if (tid < off) part[tid] += part[tid + off];
-    __syncthreads();
-  }
-  const long long r_rem = r_old - part[0];
-  __syncthreads();
-  part[tid] = bsum;
-  __syncthreads();
-  for (int off = 128; off > 0; off >>= 1) {
-    if (tid < off) part[tid] += part[tid + off];
-    __syncthreads();
-  }
-  const long long below = part[0];
+  const long long r_rem = r_old - block_sum<1024>(sum);
+  const long long below = block_sum<1024>(bsum);
   const bool none = r_rem <= 0;
   BinSel r;
   r.bin = -1;
-  if (!none && pred_try) r = block_select_bin(hist_w, 2048, r_rem - below);
+  if (!none && pred_try) r = block_select_bin<1024>(hist_w, 2048, r_rem - below);
   if (tid == 0) {
     st->r_rem = r_rem;
     st->none = none ? 1 : 0;
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256) void k_sel_start(SelState* __restrict__ st, in
     st->prefix0 = hit ? win_lo + (unsigned int)r.bin : 0u;
     st->rank0 = hit ? r_rem - below - r.before : r_rem;
   }
-  for (int e = tid; e < 4 * 2048; e += 256) hist_w[e] = 0u;
+  for (int e = tid; e < 4 * 2048; e += 1024) hist_w[e] = 0u;
 }
 
 // One wavefront per row; lanes stride over the residual columns (16 bytes per lane when the
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
   int shift = 0;
   if (PASS == 1) {
     const long long rank0 = st->rank0;
-    const BinSel r = block_select_bin(hist_in, 2048, rank0);
+    const BinSel r = block_select_bin<256>(hist_in, 2048, rank0);
     prefix = (unsigned int)r.bin;
     if (blockIdx.x == 0 && tid == 0) {
       st->prefix1 = prefix;
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, i
       shift = 4;
     } else {
       const long long rank1 = st->rank1;
-      const BinSel r = block_select_bin(hist_in, 2048, rank1);
+      const BinSel r = block_select_bin<256>(hist_in, 2048, rank1);
       prefix = (st->prefix1 << 11) | (unsigned int)r.bin;
       rank2 = rank1 - r.before;
       shift = 10;
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
   }
   const int shift = st->shift;
   const long long rank2 = st->rank2;
-  const BinSel r = block_select_bin(hist_in, 1 << shift, rank2);
+  const BinSel r = block_select_bin<256>(hist_in, 1 << shift, rank2);
   const unsigned int tau = (st->prefix2 << shift) | (unsigned int)r.bin;
   const long long rank_eq = rank2 - r.before;  // keys equal to tau that are removed
   const bool all = rank_eq == (long long)r.count;
@@ -1785,7 +1785,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       unsigned int* hist_a = w.hist + 2048;
       unsigned int* hist_b = w.hist + 2 * 2048;
       unsigned int* hist_c = w.hist + 3 * 2048;
-      hipLaunchKernelGGL(k_sel_start, dim3(1), dim3(256), 0, s, w.st, j1 == 0 ? 1 : 0, w.row_cand, c,
+      hipLaunchKernelGGL(k_sel_start, dim3(1), dim3(1024), 0, s, w.st, j1 == 0 ? 1 : 0, w.row_cand, c,
                          w.hist, w.below_part, win_parts);
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
                          nullptr, hist_a, w.row_cand, sel_vec);
