@@ -415,25 +415,23 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
 // (row, column) order).  Nothing to do when every key at the threshold is removed.
 __global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int64_t c,
                                                    const SelState* __restrict__ st) {
-  __shared__ long long part[1024];
-  const int tid = threadIdx.x;
+  __shared__ long long wtot[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (st->none || st->ties_all) return;
   const int64_t per = (c + 1023) / 1024;
   const int64_t lo = tid * per, hi = min(c, lo + per);
   long long s = 0;
   for (int64_t i = lo; i < hi; ++i) s += row_eq[i];
-  part[tid] = s;
-  __syncthreads();
-  if (tid == 0) {
-    long long run = 0;
-    for (int t = 0; t < 1024; ++t) {
-      const long long v = part[t];
-      part[t] = run;
-      run += v;
-    }
+  long long incl = s;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long t = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += t;
   }
+  if (lane == 63) wtot[wave] = incl;
   __syncthreads();
-  long long run = part[tid];
+  long long run = incl - s;
+  for (int v = 0; v < wave; ++v) run += wtot[v];
   for (int64_t i = lo; i < hi; ++i) {
     const int v = row_eq[i];
     row_eq[i] = (int)min(run, (long long)0x7fffffff);
