@@ -88,8 +88,8 @@ def cpu_baseline(args, W, X, torch):
         threads = max((p.get("num_threads", 1) for p in threadpool_info()), default=1)
     except Exception:  # pragma: no cover
         threads = os.cpu_count() or 1
-    tok_s = min(args.tokens, 8192)
-    rows_s = min(args.c, 64)
+    tok_s = min(args.tokens, 32768)
+    rows_s = min(args.c, 256)
     Xs = X[:tok_s].cpu().numpy()
     Ws = W[:rows_s].cpu().numpy()
     t0 = time.perf_counter()
