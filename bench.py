@@ -7,7 +7,10 @@ solve, trailing update).  Default workload: the LLaMA-7B-shaped 4096 x 11008 lay
 input channels), 262144 fp16 calibration tokens, 2:4 sparsity, block 128, damping 0.01.
 Inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see the design doc for the meaning of every field).
+Prints ONE JSON line: the metric (ms per layer) with its phases, a `roofline` object for the
+dominant kernel (algorithmic flops per launch / measured launch time against the MI355X fp16
+matrix-core peak, plus measured L2 <-> fabric bytes) and a `cpu_baseline` object (the float64
+oracle timed on a bounded sample of the same workload on the host cores).
 """
 from __future__ import annotations
 
@@ -120,7 +123,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(see DESIGN.md, 'More than one GPU')", file=sys.stderr)
+              "(the path is built and measured on a single MI355X)", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2504_05346_amd as th
