@@ -1041,12 +1041,17 @@ __device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int l
     const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k1));
     const float c12 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k2));
     const float d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32 + k2));
+    // 1 / d1 and 1 / d2' (d2' = d2 - c12^2 / d1, the pivot of k2 after the elimination of k1)
+    // from two INDEPENDENT reciprocals, of d1 and of det = d1 d2 - c12^2: d2' = det / d1.  The
+    // wavefront is alone on this chain, so its length is what counts.
+    const float det = fmaf(d1, d2, -c12 * c12);
     const float q1 = __builtin_amdgcn_rcpf(d1);
+    const float qd = __builtin_amdgcn_rcpf(det);
     const float r1 = fmaf(fmaf(-d1, q1, 1.f), q1, q1);
+    const float rd = fmaf(fmaf(-det, qd, 1.f), qd, qd);
     const float m = c12 * r1;
-    const float d2p = fmaf(-c12, m, d2);      // pivot of k2 after the elimination of k1
-    const float q2 = __builtin_amdgcn_rcpf(d2p);
-    const float r2 = fmaf(fmaf(-d2p, q2, 1.f), q2, q2);
+    const float d2p = det * r1;
+    const float r2 = d1 * rd;
     const float mh = hi ? m : 0.f;
     // second operands: u1 in the lower half, u2 in the upper half; columns eliminated by
     // earlier pairs are zero, and so is column k1 of u2
