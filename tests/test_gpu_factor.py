@@ -14,7 +14,7 @@ def _h(b, T=None, rho=0.7, seed=0, outliers=False):
     return orc.hessian(X).astype(np.float32)
 
 
-@pytest.mark.parametrize("b", [128, 200, 512, 1000, 1408])
+@pytest.mark.parametrize("b", [128, 200, 512, 640, 1000, 1408, 2432])
 def test_factor_matches_oracle(b):
     from tests.gpu_util import gpu_factor
     print(f"factor b={b}", flush=True)
