@@ -296,6 +296,26 @@ def test_exact_ties_follow_row_major_order(B):
     np.testing.assert_array_equal(Mg, orc.nm_mask(W, np.diag(H32), 2, 4))
 
 
+def test_threshold_jumps_between_blocks():
+    # Column blocks of very different scale: the global threshold moves by orders of magnitude
+    # from block to block, far outside the window predicted from the previous block's, so every
+    # block after the first takes the full radix passes; the third block loses all its 128
+    # columns in every row (s = B), the second nearly none.
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(96, 512, 2048, "f32", rho=0.0, seed=11)
+    scale = np.repeat(np.array([1.0, 300.0, 0.01, 20.0], dtype=np.float32), 128)
+    W = (W * scale).astype(np.float32)
+    print("threshold jumps", flush=True)
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128)
+    assert info == 0
+    Wo, Mo, margins = orc.prune_unstructured(W, H32.astype(np.float64), 0.5, 128, 0.01,
+                                             return_margins=True)
+    assert margins.min() > 2e-5, "seed has a near-tie; pick another"
+    per_block = Mo.reshape(96, 4, 128).sum(axis=(0, 2))
+    assert per_block[2] == 96 * 128 and per_block[1] < 96
+    _check(W, H32, Wg, Mg, Wo, Mo)
+
+
 def test_sparsity_edge_values():
     from tests.gpu_util import gpu_prune
     W, H32 = _layer(16, 128, 512, "f32", seed=7)
