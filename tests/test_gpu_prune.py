@@ -296,6 +296,33 @@ def test_exact_ties_follow_row_major_order(B):
     np.testing.assert_array_equal(Mg, orc.nm_mask(W, np.diag(H32), 2, 4))
 
 
+@pytest.mark.parametrize("mode", ["unstructured", "nm"])
+def test_seventeen_row_tiles(mode):
+    # 2176 rows = 17 row tiles of the trailing update: its tile order by XCD (bands of
+    # ceil(17 / 8) = 3 row tiles, the last XCDs with a short band or none) is only used from 16
+    # row tiles on.
+    from tests.gpu_util import gpu_prune
+    c, b = 2176, 384
+    W, H32 = _layer(c, b, 1536, "f32", rho=0.7, seed=21)
+    print(f"17 row tiles {mode}", flush=True)
+    H = H32.astype(np.float64)
+    if mode == "nm":
+        Wg, Mg, info = gpu_prune(W, H32, mode="nm", n=2, m=4, B=128)
+        Wo, Mo = orc.prune_nm(W, H, 2, 4, 128, 0.01)
+        assert np.all(Mg.reshape(c, b // 4, 4).sum(axis=2) == 2)
+    else:
+        Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128)
+        Wo, Mo = orc.prune_unstructured(W, H, 0.5, 128, 0.01)
+        assert int(Mg.sum()) == orc.num_to_remove(0.5, c, b)
+    assert info == 0
+    # fp32 against fp64 weights after the updates: a few near-ties may fall the other way
+    assert np.mean(Mg != Mo) < 2e-4
+    same = np.all(Mg == Mo, axis=1)
+    assert same.mean() > 0.9
+    assert _rel(Wg[same], Wo[same]) < 1e-3
+    _check(W, H32, Wg, Mg, Wo, Mo, exact_mask=False)
+
+
 def test_threshold_jumps_between_blocks():
     # Column blocks of very different scale: the global threshold moves by orders of magnitude
     # from block to block, far outside the window predicted from the previous block's, so every
