@@ -13,40 +13,69 @@
 // factorisation leaves in its workspace (U' = J L^{-1} J).  So: two rankings, one symmetric
 // gather, the factorisation, two matrix products, one scatter.  Nothing of W is permuted in
 // place; sigma only addresses columns.
+#include <algorithm>
 #include <cmath>
 
 #include "common.h"
 
 namespace thanos {
 
-// v[j] = H[j][j] * sum over non-skipped rows of W[i][j]^2 (fp64 sum in row order).
-__global__ __launch_bounds__(256) void k_col_loss(const float* __restrict__ W,
-                                                  const float* __restrict__ H, int64_t c,
-                                                  int64_t b, const uint8_t* __restrict__ skip,
-                                                  float* __restrict__ v) {
+// Column losses v[j] = H[j][j] * sum over non-skipped rows of W[i][j]^2, in two steps: fp64
+// partial sums over chunks of rows (blockIdx.y), then the sum of the partials in chunk order.
+// The second step also clears the rank counters of k_col_rank.
+__global__ __launch_bounds__(256) void k_col_loss_part(const float* __restrict__ W, int64_t c,
+                                                       int64_t b, int64_t rows_per_chunk,
+                                                       const uint8_t* __restrict__ skip,
+                                                       double* __restrict__ part) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (j >= b) return;
+  const int64_t i0 = (int64_t)blockIdx.y * rows_per_chunk, i1 = min(c, i0 + rows_per_chunk);
   double acc = 0.0;
-  for (int64_t i = 0; i < c; ++i) {
+  for (int64_t i = i0; i < i1; ++i) {
     if (skip && skip[i]) continue;
     const double w = (double)W[i * b + j];
     acc += w * w;
   }
-  v[j] = (float)(acc * (double)H[j * b + j]);
+  part[(int64_t)blockIdx.y * b + j] = acc;
 }
 
-// sigma[rank of j in ascending (v, j)] = j.
-__global__ __launch_bounds__(256) void k_col_order(const float* __restrict__ v, int64_t b,
-                                                   int* __restrict__ sigma) {
+__global__ __launch_bounds__(256) void k_col_loss_fin(const double* __restrict__ part,
+                                                      const float* __restrict__ H, int64_t b,
+                                                      int nchunk, float* __restrict__ v,
+                                                      int* __restrict__ rank) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= b) return;
+  double acc = 0.0;
+  for (int ch = 0; ch < nchunk; ++ch) acc += part[(int64_t)ch * b + j];
+  v[j] = (float)(acc * (double)H[j * b + j]);
+  rank[j] = 0;
+}
+
+// rank[j] = number of columns before j in ascending (v, j) order; every workgroup counts one
+// chunk of 2048 competitors (blockIdx.y) for its 256 columns (integer atomics: order-free).
+__global__ __launch_bounds__(256) void k_col_rank(const float* __restrict__ v, int64_t b,
+                                                  int* __restrict__ rank) {
+  __shared__ float vs[2048];
+  const int64_t k0 = (int64_t)blockIdx.y * 2048;
+  const int nk = (int)min((int64_t)2048, b - k0);
+  for (int e = threadIdx.x; e < nk; e += 256) vs[e] = v[k0 + e];
+  __syncthreads();
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (j >= b) return;
   const float mine = v[j];
-  int64_t rank = 0;
-  for (int64_t k = 0; k < b; ++k) {
-    const float o = v[k];
-    rank += (o < mine || (o == mine && k < j)) ? 1 : 0;
+  int cnt = 0;
+  for (int e = 0; e < nk; ++e) {
+    const float o = vs[e];
+    cnt += (o < mine || (o == mine && k0 + e < j)) ? 1 : 0;
   }
-  sigma[rank] = (int)j;
+  if (cnt) atomicAdd(&rank[j], cnt);
+}
+
+// sigma[rank[j]] = j (rank is sigma's inverse).
+__global__ __launch_bounds__(256) void k_col_order(const int* __restrict__ rank, int64_t b,
+                                                   int* __restrict__ sigma) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j < b) sigma[rank[j]] = (int)j;
 }
 
 // Hp[x][y] = H_sym[sigma[x]][sigma[y]] for y <= x (H given by its lower triangle).
@@ -79,20 +108,23 @@ __global__ __launch_bounds__(256) void k_rev_L(const float* __restrict__ L, int6
   M[x * s + y] = (x <= y) ? L[(b - 1 - x) * ld + (b - 1 - y)] : 0.f;
 }
 
-// Non-skipped rows: W[i][sigma[pos]] = 0 for pos < s, else -= T[i][pos]; mask accordingly.
+// Non-skipped rows: column j sits at position pos = rank[j] of the permuted order;
+// W[i][j] = 0 for pos < s, else -= T[i][pos]; mask accordingly.  (Threads run over the natural
+// columns: W and the mask are written in whole rows, only T is gathered.)
 __global__ __launch_bounds__(256) void k_struct_apply(float* __restrict__ W,
                                                       const float* __restrict__ T, int64_t b,
-                                                      const int* __restrict__ sigma, int64_t s,
+                                                      const int* __restrict__ rank, int64_t s,
                                                       const uint8_t* __restrict__ skip,
                                                       uint8_t* __restrict__ mask) {
-  const int64_t pos = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t i = blockIdx.y;
-  if (pos >= b) return;
-  const int64_t idx = i * b + sigma[pos];
+  if (j >= b) return;
+  const int64_t idx = i * b + j;
   if (skip && skip[i]) {
     mask[idx] = 0;
     return;
   }
+  const int64_t pos = rank[j];
   if (pos < s) {
     W[idx] = 0.f;
     mask[idx] = 1;
@@ -136,7 +168,7 @@ size_t structured_workspace_bytes(int64_t c, int64_t b) {
   n += align_up((size_t)c * b * 4, 256);      // Z
   n += align_up((size_t)b * b * 4, 256);      // U'
   n += 2 * align_up((size_t)b * 4, 256);      // v, xnorm2'
-  n += align_up((size_t)b * 4, 256);          // sigma
+  n += 2 * align_up((size_t)b * 4, 256);      // sigma and its inverse
   n += align_up((size_t)c * 4, 256);          // h
   n += align_up((size_t)c, 256);              // row_skip
   n += align_up(factor_workspace_bytes(b), 256);
@@ -155,6 +187,7 @@ thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int
   float* v = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
   float* xn2 = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
   int* sigma = reinterpret_cast<int*>(carve(p, (size_t)b * 4));
+  int* rank = reinterpret_cast<int*>(carve(p, (size_t)b * 4));
   float* h = reinterpret_cast<float*>(carve(p, (size_t)c * 4));
   uint8_t* skip = reinterpret_cast<uint8_t*>(carve(p, (size_t)c));
   void* fws = p;
@@ -177,10 +210,20 @@ thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int
     skip_c = skip;
   }
   const unsigned bb = (unsigned)ceil_div(b, 256);
-  hipLaunchKernelGGL(k_col_loss, dim3(bb), dim3(256), 0, st, W, H, c, b, skip_c, v);
-  THANOS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_col_order, dim3(bb), dim3(256), 0, st, v, b, sigma);
-  THANOS_LAUNCH_CHECK();
+  {
+    // partial sums live in the (still unused) buffer of U': nchunk * b doubles <= b * b floats
+    int nchunk = (int)std::max<int64_t>(1, std::min<int64_t>(32, c / 64));
+    nchunk = (int)std::min<int64_t>(nchunk, std::max<int64_t>(1, b / 2));
+    const int64_t rpc = ceil_div(c, nchunk);
+    double* part = reinterpret_cast<double*>(U);
+    hipLaunchKernelGGL(k_col_loss_part, dim3(bb, (unsigned)nchunk), dim3(256), 0, st, W, c, b, rpc,
+                       skip_c, part);
+    hipLaunchKernelGGL(k_col_loss_fin, dim3(bb), dim3(256), 0, st, part, H, b, nchunk, v, rank);
+    hipLaunchKernelGGL(k_col_rank, dim3(bb, (unsigned)ceil_div(b, 2048)), dim3(256), 0, st, v, b,
+                       rank);
+    hipLaunchKernelGGL(k_col_order, dim3(bb), dim3(256), 0, st, rank, b, sigma);
+    THANOS_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(k_permute_sym, dim3(bb, (unsigned)b), dim3(256), 0, st, H, b, sigma, HB);
   THANOS_LAUNCH_CHECK();
   thanos_status e = factor(st, HB, b, damping, U, xn2, fws, info);
@@ -201,7 +244,7 @@ thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int
     e = gemm_f32(st, false, true, c, b, s, 1.f, Z, s, U, b, 0.f, T, b, false);
     if (e != THANOS_OK) return e;
   }
-  hipLaunchKernelGGL(k_struct_apply, dim3(bb, (unsigned)c), dim3(256), 0, st, W, T, b, sigma,
+  hipLaunchKernelGGL(k_struct_apply, dim3(bb, (unsigned)c), dim3(256), 0, st, W, T, b, rank,
                      (int64_t)s_cols, skip_c, mask);
   THANOS_LAUNCH_CHECK();
   if (W_cast) {
