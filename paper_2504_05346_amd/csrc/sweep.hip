@@ -1525,15 +1525,21 @@ __global__ __launch_bounds__(256) void k_rowdot(const float* __restrict__ T,
 // skip[i] = 1 for the n_out rows with the largest (h, row) (ascending order, ties by row index).
 __global__ __launch_bounds__(256) void k_row_rank(const float* __restrict__ h, int64_t c,
                                                   int64_t n_out, uint8_t* __restrict__ skip) {
+  __shared__ float hs[2048];  // competitors, one chunk at a time
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= c) return;
-  const float mine = h[i];
+  const float mine = (i < c) ? h[i] : 0.f;
   int64_t rank = 0;
-  for (int64_t k = 0; k < c; ++k) {
-    const float o = h[k];
-    rank += (o < mine || (o == mine && k < i)) ? 1 : 0;
+  for (int64_t k0 = 0; k0 < c; k0 += 2048) {
+    const int nk = (int)min((int64_t)2048, c - k0);
+    __syncthreads();
+    for (int e = threadIdx.x; e < nk; e += 256) hs[e] = h[k0 + e];
+    __syncthreads();
+    for (int e = 0; e < nk; ++e) {
+      const float o = hs[e];
+      rank += (o < mine || (o == mine && k0 + e < i)) ? 1 : 0;
+    }
   }
-  skip[i] = rank >= c - n_out ? 1 : 0;
+  if (i < c) skip[i] = rank >= c - n_out ? 1 : 0;
 }
 
 // skip[i] = 1 for the n_out rows of W (c x b fp32) with the largest loss W_i H W_i^T (H: lower
