@@ -15,8 +15,9 @@
  *     buffers; the library allocates no device memory and keeps no state between calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
  *     enqueued asynchronously on it; nothing synchronises with the host.  thanos_factor and
- *     thanos_prune_layer also create one short-lived helper stream (default priority) per call,
- *     forked from and joined back into `stream` with events; it is destroyed before they return.
+ *     thanos_prune_layer also create short-lived helper streams (default priority; two for the
+ *     factorisation, one for the sweep) per call, forked from and joined back into `stream`
+ *     with events; they are destroyed before the call returns.
  *   - The return value covers argument checks and launch errors only.  Numerical failure
  *     (a non-positive pivot) is reported through the device word `info_dev`, which the
  *     caller reads after synchronising the stream.
