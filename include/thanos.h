@@ -13,11 +13,14 @@
  * Conventions
  *   - Every data pointer is a DEVICE pointer unless it says "host".  The caller owns all
  *     buffers; the library allocates no device memory and keeps no state between calls.
- *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
- *     enqueued asynchronously on it; nothing synchronises with the host.  thanos_factor and
- *     thanos_prune_layer also create short-lived helper streams (default priority; two for the
- *     factorisation, one for the sweep) per call, forked from and joined back into `stream`
- *     with events; they are destroyed before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All kernels are
+ *     enqueued asynchronously; results are ordered after the call on `stream`.  thanos_factor
+ *     and thanos_prune_layer create host-side HIP objects per call: helper streams (default
+ *     priority; two for the factorisation, one for the sweep) and a few events per block
+ *     column, forked from and joined back into `stream`, and destroyed before the call returns
+ *     (the runtime may wait for a helper stream to drain when it destroys it).  On an error
+ *     return every helper stream is joined into `stream` first, so work already enqueued is
+ *     ordered before anything the caller enqueues on `stream` afterwards.
  *   - The return value covers argument checks and launch errors only.  Numerical failure
  *     (a non-positive pivot) is reported through the device word `info_dev`, which the
  *     caller reads after synchronising the stream.
@@ -109,7 +112,9 @@ thanos_status thanos_hessian_accumulate(float* H, int64_t b, const void* Xc, tha
  * triangle set to 0) and xnorm2 (b).  U must not alias H.  ws: thanos_factor_workspace_bytes(b)
  * bytes of scratch.  info_dev: device int32; set to 0, or to k > 0 if the pivot of column k
  * (1-based; columns are eliminated from the last to the first) was not positive, in which
- * case U is meaningless.  Arithmetic: fp32 throughout (fp32 matrix-core products).
+ * case U is meaningless.  Arithmetic: fp32 storage; matrix products are computed on the bf16
+ * matrix cores from operands split into three bf16 terms each (six partial products summed in
+ * fp32, error of the order of one fp32 rounding per product), everything else in plain fp32.
  */
 thanos_status thanos_factor(const float* H, int64_t b, float damping, float* U, float* xnorm2,
                             void* ws, size_t ws_bytes, int32_t* info_dev, void* stream);
@@ -117,7 +122,8 @@ size_t thanos_factor_workspace_bytes(int64_t b);
 
 /*
  * Column-block sweep: Alg. 1 (unstructured, global residual mask psi_X, Sec. 4.4) or the n:m
- * algorithm of App. G.4.4 with alpha = 0 (no outlier rows).  For every block of B columns,
+ * algorithm of App. G.4.4 (with its outlier rows when opts->outlier_fraction > 0); structured
+ * pruning (Alg. 2) is reached through the same call.  For every block of B columns,
  * left to right: choose the block mask M from the metric |W_ij| * sqrt(xnorm2_j) of the
  * CURRENT weights, then for every row with q = phi(M_i:) (Sec. 4.5) solve lambda R_hat = u and
  * apply Delta = -u R_hat^{-1} R to all columns from the block start to b (Sec. 4.1, eqs. (R),
@@ -133,7 +139,7 @@ size_t thanos_factor_workspace_bytes(int64_t b);
  * Ties in the metric are broken by ascending (row, column).
  * Errors: INVALID_ARG (NULL, sizes, n/m/B constraints, p or alpha outside [0,1), alpha > 0
  * without H), UNSUPPORTED (block_size beyond the limits above, m > 16, alpha > 0 with
- * THANOS_UNSTRUCTURED),
+ * THANOS_UNSTRUCTURED or with mask_in, b > 65535, c > 2^24, THANOS_STRUCTURED with c > 65535),
  * WORKSPACE, HIP.
  */
 thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,

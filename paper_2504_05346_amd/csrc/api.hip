@@ -8,11 +8,12 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers);
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
-                    void* W_cast, uint8_t* mask, void* ws, int32_t* info);
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream);
 size_t structured_workspace_bytes(int64_t c, int64_t b);
 thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                          const float* H, float damping, long long s_cols, long long n_out,
-                         float* W, void* W_cast, uint8_t* mask, void* ws, int32_t* info);
+                         float* W, void* W_cast, uint8_t* mask, void* ws, int32_t* info,
+                         bool single_stream);
 __global__ void k_zero_info(int32_t* info) { *info = 0; }
 }  // namespace thanos
 
@@ -58,7 +59,7 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
     if (num_columns_to_remove(o->sparsity, o->outlier_fraction, b) > b)
       return THANOS_ERR_INVALID_ARG;  // p / (1 - alpha) > 1
     if (o->factor_in || o->mask_in) return THANOS_ERR_UNSUPPORTED;  // the factor is of H[sigma,sigma]
-    (void)c;
+    if (c > 65535) return THANOS_ERR_UNSUPPORTED;  // its row-wise kernels put the row in grid.y
     return THANOS_OK;
   }
   if (o->block_size < 1) return THANOS_ERR_INVALID_ARG;
@@ -71,6 +72,8 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
   }
   if (o->factor_in && !o->xnorm2_in) return THANOS_ERR_INVALID_ARG;
   if (o->outlier_fraction > 0.0 && o->mode != THANOS_NM) return THANOS_ERR_UNSUPPORTED;
+  // a given mask already says which rows are pruned; the outlier rows are a selection rule
+  if (o->outlier_fraction > 0.0 && o->mask_in) return THANOS_ERR_UNSUPPORTED;
   // the per-row systems must fit the solver: at most 256 unknowns, blocks of at most 512 columns
   if (o->mode == THANOS_NM && !o->mask_in) {
     if (o->block_size > 512 || o->block_size / o->m * o->n > 256) return THANOS_ERR_UNSUPPORTED;
@@ -131,28 +134,33 @@ size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opt
   return n;
 }
 
-thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
-                                 const float* H, const thanos_prune_opts* opts, float* W_out,
-                                 void* W_out_cast, uint8_t* mask_out, void* ws, size_t ws_bytes,
-                                 int32_t* info_dev, void* stream) {
+// Argument checks shared by the two sweep entry points (everything but the workspace).
+static thanos_status check_prune_args(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                      const float* H, const thanos_prune_opts* opts,
+                                      const float* W_out, const uint8_t* mask_out,
+                                      const int32_t* info_dev) {
   if (!W_in || !W_out || !mask_out || !info_dev || c <= 0 || b <= 0 || !dtype_ok(wdt))
     return THANOS_ERR_INVALID_ARG;
   thanos_status st = check_opts(opts, c, b);
   if (st != THANOS_OK) return st;
   if (!opts->factor_in && !H) return THANOS_ERR_INVALID_ARG;
   if (opts->outlier_fraction > 0.0 && !H) return THANOS_ERR_INVALID_ARG;  // row losses need H
+  if (opts->mode == THANOS_STRUCTURED && !H) return THANOS_ERR_INVALID_ARG;
   if (b > 65535 || c > ((int64_t)1 << 24)) return THANOS_ERR_UNSUPPORTED;
-  if (!ws || ws_bytes < thanos_prune_workspace_bytes(c, b, opts)) return THANOS_ERR_WORKSPACE;
-  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
-  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  if (opts->mode == THANOS_STRUCTURED) {
-    if (!H) return THANOS_ERR_INVALID_ARG;
+  return THANOS_OK;
+}
+
+// Factor (unless given) and sweep with `ws` as the workspace (checked by the caller).
+static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                          const float* H, const thanos_prune_opts* opts,
+                                          float* W_out, void* W_out_cast, uint8_t* mask_out,
+                                          void* ws, int32_t* info_dev, hipStream_t s,
+                                          bool single_stream) {
+  if (opts->mode == THANOS_STRUCTURED)
     return structured(s, W_in, wdt, c, b, H, opts->damping,
                       num_columns_to_remove(opts->sparsity, opts->outlier_fraction, b),
                       num_outlier_rows(opts->outlier_fraction, c), W_out, W_out_cast, mask_out, ws,
-                      info_dev);
-  }
-
+                      info_dev, single_stream);
   char* p = reinterpret_cast<char*>(ws);
   void* sweep_ws = p;
   p += sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
@@ -163,7 +171,7 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
     p += align_up((size_t)b * b * sizeof(float), 256);
     float* xw = reinterpret_cast<float*>(p);
     p += align_up((size_t)b * sizeof(float), 256);
-    st = factor(s, H, b, opts->damping, Uw, xw, p, info_dev);
+    thanos_status st = factor(s, H, b, opts->damping, Uw, xw, p, info_dev, single_stream);
     if (st != THANOS_OK) return st;
     U = Uw;
     xn2 = xw;
@@ -175,7 +183,19 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
       (opts->mode == THANOS_UNSTRUCTURED) ? num_to_remove(opts->sparsity, c, b) : 0;
   const long long n_out = num_outlier_rows(opts->outlier_fraction, c);
   return sweep(s, W_in, wdt, c, b, H, U, xn2, opts, r_total, n_out, W_out, W_out_cast, mask_out,
-               sweep_ws, info_dev);
+               sweep_ws, info_dev, single_stream);
+}
+
+thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                 const float* H, const thanos_prune_opts* opts, float* W_out,
+                                 void* W_out_cast, uint8_t* mask_out, void* ws, size_t ws_bytes,
+                                 int32_t* info_dev, void* stream) {
+  thanos_status st = check_prune_args(W_in, wdt, c, b, H, opts, W_out, mask_out, info_dev);
+  if (st != THANOS_OK) return st;
+  if (!ws || ws_bytes < thanos_prune_workspace_bytes(c, b, opts)) return THANOS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
+  return prune_with_workspace(W_in, wdt, c, b, H, opts, W_out, W_out_cast, mask_out, ws, info_dev,
+                              reinterpret_cast<hipStream_t>(stream), false);
 }
 
 }  // extern "C"

@@ -27,32 +27,92 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// A second stream (default priority) forked from and joined back into the caller's stream with
-// events, used to run a long, throughput-bound update next to a chain of short, latency-bound
-// kernels.  Host objects only; created and destroyed inside one call.
-struct AuxStream {
+// A helper stream (default priority) of one call, forked from and joined back into the caller's
+// stream with events; it runs a long, throughput-bound update next to a chain of short,
+// latency-bound kernels.  Host objects only, created and destroyed inside the call.
+//   fork(i)    the helper waits for everything the caller's stream holds now (event i)
+//   record(i)  event i <- everything the helper holds now; no launch on the helper may follow
+//              a record without a new fork
+//   join(i)    the caller's stream waits for event i
+// If the object is destroyed while forked work has not been joined (an error return between a
+// fork and its join), the destructor joins it first, so that the caller's stream never runs
+// ahead of kernels that still use the caller's buffers.
+// inline_mode: there is no helper: `stream` IS the caller's stream and fork / record / join do
+// nothing (one in-order stream runs the kernels in the order the host enqueues them, and that
+// order respects every dependency the events express).  Nothing is created or destroyed.
+class AuxStream {
+ public:
   hipStream_t stream = nullptr;
-  hipEvent_t* ev = nullptr;
-  int nev = 0;
   bool ok = false;
-  explicit AuxStream(int n_events) {
+  AuxStream(hipStream_t caller, int n_events, bool inline_mode)
+      : caller_(caller), inline_(inline_mode) {
+    if (inline_) {
+      stream = caller;
+      ok = true;
+      return;
+    }
+    if (n_events <= 0) {  // no fork will happen: nothing to create
+      inline_ = true;
+      stream = caller;
+      ok = true;
+      return;
+    }
     if (hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) != hipSuccess) {
       stream = nullptr;
       return;
     }
-    ev = new hipEvent_t[n_events > 0 ? n_events : 1];
-    for (nev = 0; nev < n_events; ++nev)
-      if (hipEventCreateWithFlags(&ev[nev], hipEventDisableTiming) != hipSuccess) return;
+    ev_ = new hipEvent_t[n_events + 1];  // the last one serves the destructor
+    for (nev_ = 0; nev_ < n_events + 1; ++nev_)
+      if (hipEventCreateWithFlags(&ev_[nev_], hipEventDisableTiming) != hipSuccess) return;
     ok = true;
   }
+  thanos_status fork(int i) {
+    if (inline_) return THANOS_OK;
+    if (i < 0 || i >= nev_ - 1) return THANOS_ERR_HIP;
+    if (hipEventRecord(ev_[i], caller_) != hipSuccess) return THANOS_ERR_HIP;
+    if (hipStreamWaitEvent(stream, ev_[i], 0) != hipSuccess) return THANOS_ERR_HIP;
+    open_ = true;
+    last_rec_ = -1;
+    return THANOS_OK;
+  }
+  thanos_status record(int i) {
+    if (inline_) return THANOS_OK;
+    if (i < 0 || i >= nev_ - 1) return THANOS_ERR_HIP;
+    if (hipEventRecord(ev_[i], stream) != hipSuccess) return THANOS_ERR_HIP;
+    last_rec_ = i;
+    return THANOS_OK;
+  }
+  thanos_status join(int i) {
+    if (inline_) return THANOS_OK;
+    if (i < 0 || i >= nev_ - 1) return THANOS_ERR_HIP;
+    if (hipStreamWaitEvent(caller_, ev_[i], 0) != hipSuccess) return THANOS_ERR_HIP;
+    if (i == last_rec_) open_ = false;
+    return THANOS_OK;
+  }
   ~AuxStream() {
-    for (int i = 0; i < nev; ++i) (void)hipEventDestroy(ev[i]);
-    delete[] ev;
+    if (inline_) return;
+    if (ok && open_ && hipEventRecord(ev_[nev_ - 1], stream) == hipSuccess)
+      (void)hipStreamWaitEvent(caller_, ev_[nev_ - 1], 0);
+    for (int i = 0; i < nev_; ++i) (void)hipEventDestroy(ev_[i]);
+    delete[] ev_;
     if (stream) (void)hipStreamDestroy(stream);
   }
   AuxStream(const AuxStream&) = delete;
   AuxStream& operator=(const AuxStream&) = delete;
+
+ private:
+  hipStream_t caller_;
+  hipEvent_t* ev_ = nullptr;
+  int nev_ = 0;
+  bool inline_;
+  bool open_ = false;  // forked work that no join covers yet
+  int last_rec_ = -1;  // event of the last record since the last fork
 };
+#define THANOS_CHECK(expr)                 \
+  do {                                     \
+    thanos_status st_ = (expr);            \
+    if (st_ != THANOS_OK) return st_;      \
+  } while (0)
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- internal entry points shared between translation units -------------------------------
@@ -78,8 +138,9 @@ thanos_status syrk_accumulate(hipStream_t s, float* H, int64_t b, const void* Xc
 // in the workspace holds the Cholesky factor L of J H_d J (U = J L^{-1} J): factor_L() returns
 // it and its leading dimension.
 size_t factor_workspace_bytes(int64_t b);
+// single_stream: no helper streams, everything on `s` in enqueue order (nothing is created).
 thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
-                     float* xnorm2, void* ws, int32_t* info);
+                     float* xnorm2, void* ws, int32_t* info, bool single_stream = false);
 const float* factor_L(const void* ws, int64_t b, int64_t* ld);
 
 // skip[i] = 1 for the n_out rows of W (c x b fp32) with the largest loss W_i H W_i^T (sweep.hip).

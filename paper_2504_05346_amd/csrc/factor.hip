@@ -453,7 +453,7 @@ size_t factor_workspace_bytes(int64_t b) {
 }
 
 thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, float* U,
-                     float* xnorm2, void* ws, int32_t* info) {
+                     float* xnorm2, void* ws, int32_t* info, bool single_stream) {
   const int64_t bp = padded(b);
   const int nb = (int)(bp / NB);
   float* lam = reinterpret_cast<float*>(ws);
@@ -480,7 +480,7 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
                                        (int)kCholDiagSmem));
   constexpr int kOuter = 4;
   const int n_outer = (nb + kOuter - 1) / kOuter;
-  AuxStream aux(2 * n_outer);
+  AuxStream aux(s, 2 * n_outer, single_stream);
   if (!aux.ok) return THANOS_ERR_HIP;
 
   // The inverse of L (recursive doubling, see k_trinv_T / k_trinv_X) does not wait for the end
@@ -498,15 +498,14 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   THANOS_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_trinv_X),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)kXSmemBytes));
-  AuxStream tri(n_outer + 1);
+  AuxStream tri(s, n_outer + 1, single_stream);
   if (!tri.ok) return THANOS_ERR_HIP;
   int tri_done = -1;  // blocks 0..tri_done have been handed to the inversion
   int tri_batches = 0;
   constexpr int tri_cap = 512;  // workgroups of one launch while the factorisation runs
   auto trinv_upto = [&](int kdone) -> thanos_status {
     // blocks <= kdone: diagonal inverse known, panel below solved (recorded on s by the caller)
-    THANOS_HIP_CHECK(hipEventRecord(tri.ev[tri_batches], s));
-    THANOS_HIP_CHECK(hipStreamWaitEvent(tri.stream, tri.ev[tri_batches], 0));
+    THANOS_CHECK(tri.fork(tri_batches));
     ++tri_batches;
     for (int S = 1; S < nb; S *= 2) {
       for (int second = 0; second < 2; ++second) {
@@ -580,8 +579,7 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
       const float* lp = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_begin * NB;
       // fork: the rest (rows and columns >= next_end) on the second stream
       if (next_end < nb) {
-        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * ob], s));
-        THANOS_HIP_CHECK(hipStreamWaitEvent(aux.stream, aux.ev[2 * ob], 0));
+        THANOS_CHECK(aux.fork(2 * ob));
         const int64_t rest = bp - (int64_t)next_end * NB;
         const float* lr = lp + ((int64_t)(next_end - ob_end) * NB) * bp;
         float* cr = Ap + ((int64_t)next_end * NB) * bp + (int64_t)next_end * NB;
@@ -590,7 +588,7 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
         if (st != THANOS_OK) return st;
       }
       // the strip of the next outer block: it was last written by the previous rest
-      if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
+      if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
       {
         const int64_t rows = bp - (int64_t)ob_end * NB;
         const int64_t cols = (int64_t)(next_end - ob_end) * NB;
@@ -599,15 +597,15 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
         if (st != THANOS_OK) return st;
       }
       if (next_end < nb) {
-        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * ob + 1], aux.stream));
+        THANOS_CHECK(aux.record(2 * ob + 1));
         pending_join = 2 * ob + 1;
       }
     }
   }
-  if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
+  if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
 
-  THANOS_HIP_CHECK(hipEventRecord(tri.ev[n_outer], tri.stream));
-  THANOS_HIP_CHECK(hipStreamWaitEvent(s, tri.ev[n_outer], 0));
+  THANOS_CHECK(tri.record(n_outer));
+  THANOS_CHECK(tri.join(n_outer));
 
   hipLaunchKernelGGL(k_reverse_out, dim3((unsigned)ceil_div(b, 256), (unsigned)b), dim3(256), 0, s,
                      Linv, bp, U, b);

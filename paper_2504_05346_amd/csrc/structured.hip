@@ -177,7 +177,8 @@ size_t structured_workspace_bytes(int64_t c, int64_t b) {
 
 thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                          const float* H, float damping, long long s_cols, long long n_out,
-                         float* W, void* W_cast, uint8_t* mask, void* ws, int32_t* info) {
+                         float* W, void* W_cast, uint8_t* mask, void* ws, int32_t* info,
+                         bool single_stream) {
   char* p = reinterpret_cast<char*>(ws);
   float* HB = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
   float* T = reinterpret_cast<float*>(carve(p, (size_t)c * b * 4));
@@ -226,7 +227,7 @@ thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int
   }
   hipLaunchKernelGGL(k_permute_sym, dim3(bb, (unsigned)b), dim3(256), 0, st, H, b, sigma, HB);
   THANOS_LAUNCH_CHECK();
-  thanos_status e = factor(st, HB, b, damping, U, xn2, fws, info);
+  thanos_status e = factor(st, HB, b, damping, U, xn2, fws, info, single_stream);
   if (e != THANOS_OK) return e;
   if (s_cols > 0) {
     const int64_t s = s_cols;

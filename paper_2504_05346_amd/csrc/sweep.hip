@@ -1719,7 +1719,7 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
-                    void* W_cast, uint8_t* mask, void* ws, int32_t* info) {
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream) {
   const int B = o->block_size;
   const bool outliers = n_out > 0;
   SweepWs w = carve_ws(ws, c, b, B, outliers);
@@ -1773,8 +1773,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   // second stream next to the (latency-bound) blocks of the next super-block.  The multipliers
   // of consecutive super-blocks alternate between two buffers.
   const int n_super = (int)ceil_div(b, (int64_t)B * super);
-  AuxStream aux(super > 1 ? 2 * n_super : 0);
-  if (super > 1 && !aux.ok) return THANOS_ERR_HIP;
+  AuxStream aux(s, super > 1 ? 2 * n_super : 0, single_stream);
+  if (!aux.ok) return THANOS_ERR_HIP;
   int pending_join = -1;
   int win_parts = 0;  // workgroups of the previous block's update (partial counts to sum)
   for (int64_t j1 = 0; j1 < b; j1 += B) {
@@ -1853,8 +1853,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       const int64_t next_end = std::min<int64_t>(b, sb_end + (int64_t)super * B);
       const int kk = (int)(sb_end - sb_start);
       if (next_end < b) {  // rest: right of the next super-block, second stream
-        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * sbi], s));
-        THANOS_HIP_CHECK(hipStreamWaitEvent(aux.stream, aux.ev[2 * sbi], 0));
+        THANOS_CHECK(aux.fork((int)(2 * sbi)));
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
                       (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
                       nullptr};
@@ -1862,7 +1861,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         launch_update(aux.stream, ua, grid);
         THANOS_LAUNCH_CHECK();
       }
-      if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
+      if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
       {  // strip: the columns of the next super-block
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
                       (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
@@ -1872,12 +1871,12 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         THANOS_LAUNCH_CHECK();
       }
       if (next_end < b) {
-        THANOS_HIP_CHECK(hipEventRecord(aux.ev[2 * sbi + 1], aux.stream));
+        THANOS_CHECK(aux.record((int)(2 * sbi + 1)));
         pending_join = (int)(2 * sbi + 1);
       }
     }
   }
-  if (pending_join >= 0) THANOS_HIP_CHECK(hipStreamWaitEvent(s, aux.ev[pending_join], 0));
+  if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
 
   if (W_cast) {
     if (wdt == THANOS_F32)
