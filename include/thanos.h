@@ -12,15 +12,18 @@
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer unless it says "host".  The caller owns all
- *     buffers; the library allocates no device memory and keeps no state between calls.
+ *     buffers; the library allocates no device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All kernels are
- *     enqueued asynchronously; results are ordered after the call on `stream`.  thanos_factor
- *     and thanos_prune_layer create host-side HIP objects per call: helper streams (default
- *     priority; two for the factorisation, one for the sweep) and a few events per block
- *     column, forked from and joined back into `stream`, and destroyed before the call returns
- *     (the runtime may wait for a helper stream to drain when it destroys it).  On an error
- *     return every helper stream is joined into `stream` first, so work already enqueued is
- *     ordered before anything the caller enqueues on `stream` afterwards.
+ *     enqueued asynchronously and the call returns without waiting for the device; results are
+ *     ordered after the call on `stream`.  thanos_factor and thanos_prune_layer run part of
+ *     their work on helper streams (default priority; two for the factorisation, one for the
+ *     sweep), forked from and joined back into `stream` with events.  These host-side HIP
+ *     objects are the only state the library keeps: a call borrows them from a per-process pool
+ *     (created on first use per device, one set per concurrently running call, never destroyed,
+ *     because destroying a stream waits for it to drain).  On an error return every helper
+ *     stream is joined into `stream` first, so work already enqueued is ordered before anything
+ *     the caller enqueues on `stream` afterwards.  Calls may be issued from several host
+ *     threads; the device current at the call must be the one `stream` belongs to.
  *   - The return value covers argument checks and launch errors only.  Numerical failure
  *     (a non-positive pivot) is reported through the device word `info_dev`, which the
  *     caller reads after synchronising the stream.

@@ -1,5 +1,9 @@
 // C ABI of libthanos: argument checks and orchestration only; all arithmetic is in the kernels.
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <mutex>
+#include <vector>
 
 #include "common.h"
 
@@ -19,32 +23,166 @@ __global__ void k_zero_info(int32_t* info) { *info = 0; }
 
 using namespace thanos;
 
-static bool dtype_ok(int d) { return d == THANOS_F32 || d == THANOS_F16 || d == THANOS_BF16; }
+// ---- pool of helper-stream contexts (see common.h) ----------------------------------------
+namespace {
+struct StreamPool {
+  std::mutex mu;
+  std::vector<StreamCtx*> idle;
+};
+StreamPool& stream_pool() {
+  static StreamPool* p = new StreamPool;  // never destroyed: no HIP call at process exit
+  return *p;
+}
+}  // namespace
 
-// r = floor(p*c*b) with p read as the short decimal it prints as: a product that lands within
-// 1e-6 below an integer is that integer (0.6 * 10 -> 6, not 5).
-static long long num_to_remove(double p, int64_t c, int64_t b) {
-  const long double x = (long double)p * (long double)c * (long double)b;
-  long long r = (long long)floorl(x);
-  if ((long double)(r + 1) - x < 1e-6L) r += 1;
-  return r;
+StreamCtx* stream_ctx_acquire(int n_events) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  StreamCtx* c = nullptr;
+  {
+    StreamPool& pool = stream_pool();
+    std::lock_guard<std::mutex> guard(pool.mu);
+    for (size_t i = 0; i < pool.idle.size(); ++i)
+      if (pool.idle[i]->device == dev) {
+        c = pool.idle[i];
+        pool.idle.erase(pool.idle.begin() + (long)i);
+        break;
+      }
+  }
+  if (!c) {
+    c = new StreamCtx;
+    c->device = dev;
+    if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess) {
+      delete c;
+      return nullptr;
+    }
+  }
+  if (c->cap < n_events) {
+    hipEvent_t* ev = new hipEvent_t[n_events];
+    for (int i = 0; i < c->nev; ++i) ev[i] = c->ev[i];
+    delete[] c->ev;
+    c->ev = ev;
+    c->cap = n_events;
+  }
+  while (c->nev < n_events) {
+    if (hipEventCreateWithFlags(&c->ev[c->nev], hipEventDisableTiming) != hipSuccess) {
+      stream_ctx_release(c);  // keeps what exists
+      return nullptr;
+    }
+    ++c->nev;
+  }
+  return c;
 }
 
-// Number of outlier rows, ceil(alpha*c), with alpha read as the short decimal it prints as: a
-// product that lands within 1e-6 above an integer is that integer (0.1 * 1000 -> 100, not 101).
+void stream_ctx_release(StreamCtx* c) {
+  if (!c) return;
+  StreamPool& pool = stream_pool();
+  std::lock_guard<std::mutex> guard(pool.mu);
+  pool.idle.push_back(c);
+}
+
+// ---- counts derived from p and alpha ------------------------------------------------------
+// p and alpha are read as the decimal they print as: the shortest decimal string that converts
+// back to the same double (0.6 means 6/10, not the binary value just below it), and the counts
+// floor(p*c*b), ceil(alpha*c), ceil(p*b/(1-alpha)) are then evaluated in exact integer
+// arithmetic.
+typedef unsigned __int128 u128;
+
+struct Decimal {  // value = mant / 10^scale
+  unsigned long long mant;
+  int scale;
+};
+
+static Decimal shortest_decimal(double x) {
+  char buf[48];
+  for (int digits = 1; digits <= 17; ++digits) {
+    snprintf(buf, sizeof buf, "%.*e", digits - 1, x);  // d.ddde[+-]xx, correctly rounded
+    if (strtod(buf, nullptr) == x) break;
+  }
+  Decimal d{0ull, 0};
+  const char* q = buf;
+  bool frac = false;
+  for (; *q && *q != 'e'; ++q) {
+    if (*q == '.') {
+      frac = true;
+      continue;
+    }
+    if (*q < '0' || *q > '9') continue;  // sign (callers pass x >= 0)
+    d.mant = d.mant * 10ull + (unsigned long long)(*q - '0');
+    if (frac) ++d.scale;
+  }
+  if (*q == 'e') d.scale -= atoi(q + 1);
+  while (d.scale < 0) {  // x < 1 in every caller, so this only normalises "0e+00"
+    d.mant *= 10ull;
+    ++d.scale;
+  }
+  while (d.scale > 0 && d.mant % 10ull == 0ull) {
+    d.mant /= 10ull;
+    --d.scale;
+  }
+  return d;
+}
+
+static bool pow10_u128(int e, u128* out) {
+  if (e < 0 || e > 38) return false;
+  u128 v = 1;
+  for (int i = 0; i < e; ++i) v *= 10;
+  *out = v;
+  return true;
+}
+
+// r = floor(p*c*b)  (Alg. 1 "r <- pcb", problem statement: floor)
+static long long num_to_remove(double p, int64_t c, int64_t b) {
+  const Decimal d = shortest_decimal(p);
+  u128 den;
+  if (!pow10_u128(d.scale, &den)) return 0;  // p < 1e-38
+  return (long long)((u128)d.mant * (u128)c * (u128)b / den);  // < 2^57 * 2^24 * 2^16
+}
+
+// Number of outlier rows, ceil(alpha*c)  (Sec. 4.7 "Outlier rows")
 static long long num_outlier_rows(double alpha, int64_t c) {
   if (!(alpha > 0.0)) return 0;
-  const long double x = (long double)alpha * (long double)c;
-  long long n = (long long)ceill(x);
-  if (x - (long double)(n - 1) < 1e-6L) n -= 1;
-  return n < 0 ? 0 : (n > c ? c : n);
+  const Decimal d = shortest_decimal(alpha);
+  u128 den;
+  if (!pow10_u128(d.scale, &den)) return 1;  // 0 < alpha*c < 1
+  const long long n = (long long)(((u128)d.mant * (u128)c + den - 1) / den);
+  return n > c ? c : n;
 }
 
-// Columns removed by the structured algorithm, ceil(p*b/(1-alpha)), decimals as above.
+static u128 gcd_u128(u128 a, u128 b) {
+  while (b != 0) {
+    const u128 t = a % b;
+    a = b;
+    b = t;
+  }
+  return a;
+}
+
+// Columns removed by the structured algorithm, ceil(p*b/(1-alpha))  (Alg. 2).
 static long long num_columns_to_remove(double p, double alpha, int64_t b) {
+  const Decimal dp = shortest_decimal(p), da = shortest_decimal(alpha > 0.0 ? alpha : 0.0);
+  u128 tp, ta;
+  if (dp.mant == 0) return 0;
+  if (pow10_u128(dp.scale, &tp) && pow10_u128(da.scale, &ta) && (u128)da.mant < ta) {
+    // p*b/(1-alpha) = (P*b*Ta) / (Tp*(Ta-A)); reduce before multiplying
+    u128 n1 = (u128)dp.mant * (u128)b, d1 = tp, n2 = ta, d2 = ta - (u128)da.mant;
+    u128 g = gcd_u128(n1, d1);
+    n1 /= g, d1 /= g;
+    g = gcd_u128(n2, d2);
+    n2 /= g, d2 /= g;
+    g = gcd_u128(n1, d2);
+    n1 /= g, d2 /= g;
+    g = gcd_u128(n2, d1);
+    n2 /= g, d1 /= g;
+    u128 num, den;
+    if (!__builtin_mul_overflow(n1, n2, &num) && !__builtin_mul_overflow(d1, d2, &den)) {
+      const u128 q = (num + den - 1) / den;
+      return q > (u128)1 << 62 ? (long long)1 << 62 : (long long)q;
+    }
+  }
+  // decimals too long for 128 bits: plain extended-precision evaluation
   const long double x = (long double)p * (long double)b / (1.0L - (long double)alpha);
-  long long n = (long long)ceill(x);
-  if (x - (long double)(n - 1) < 1e-6L) n -= 1;
+  const long long n = (long long)ceill(x);
   return n < 0 ? 0 : n;
 }
 

@@ -27,9 +27,25 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// A helper stream (default priority) of one call, forked from and joined back into the caller's
-// stream with events; it runs a long, throughput-bound update next to a chain of short,
-// latency-bound kernels.  Host objects only, created and destroyed inside the call.
+// Helper streams and their events are host objects that cost tens of microseconds to create
+// and whose destruction waits for the stream to drain (which would stall the host inside every
+// call).  They are therefore kept: a call borrows a context (one stream of default priority and
+// as many events as it needs) from a per-process pool and hands it back on return; contexts are
+// created on demand, one set per device and per concurrently running call, and live until the
+// process ends.  A context is handed back only after its work has been joined into the
+// caller's stream, so the next borrower's work is merely queued behind it.
+struct StreamCtx {
+  int device = -1;
+  hipStream_t stream = nullptr;
+  hipEvent_t* ev = nullptr;
+  int nev = 0, cap = 0;
+};
+StreamCtx* stream_ctx_acquire(int n_events);  // nullptr on failure (api.hip)
+void stream_ctx_release(StreamCtx* c);
+
+// A helper stream (default priority) for the duration of one call, forked from and joined back
+// into the caller's stream with events; it runs a long, throughput-bound update next to a chain
+// of short, latency-bound kernels.
 //   fork(i)    the helper waits for everything the caller's stream holds now (event i)
 //   record(i)  event i <- everything the helper holds now; no launch on the helper may follow
 //              a record without a new fork
@@ -39,38 +55,29 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // ahead of kernels that still use the caller's buffers.
 // inline_mode: there is no helper: `stream` IS the caller's stream and fork / record / join do
 // nothing (one in-order stream runs the kernels in the order the host enqueues them, and that
-// order respects every dependency the events express).  Nothing is created or destroyed.
+// order respects every dependency the events express).  Nothing is created or borrowed.
 class AuxStream {
  public:
   hipStream_t stream = nullptr;
   bool ok = false;
   AuxStream(hipStream_t caller, int n_events, bool inline_mode)
-      : caller_(caller), inline_(inline_mode) {
-    if (inline_) {
+      : caller_(caller), inline_(inline_mode || n_events <= 0) {
+    if (inline_) {  // also when no fork will happen
       stream = caller;
       ok = true;
       return;
     }
-    if (n_events <= 0) {  // no fork will happen: nothing to create
-      inline_ = true;
-      stream = caller;
-      ok = true;
-      return;
-    }
-    if (hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) != hipSuccess) {
-      stream = nullptr;
-      return;
-    }
-    ev_ = new hipEvent_t[n_events + 1];  // the last one serves the destructor
-    for (nev_ = 0; nev_ < n_events + 1; ++nev_)
-      if (hipEventCreateWithFlags(&ev_[nev_], hipEventDisableTiming) != hipSuccess) return;
+    ctx_ = stream_ctx_acquire(n_events + 1);  // the last event serves the destructor
+    if (!ctx_) return;
+    stream = ctx_->stream;
+    nev_ = n_events + 1;
     ok = true;
   }
   thanos_status fork(int i) {
     if (inline_) return THANOS_OK;
     if (i < 0 || i >= nev_ - 1) return THANOS_ERR_HIP;
-    if (hipEventRecord(ev_[i], caller_) != hipSuccess) return THANOS_ERR_HIP;
-    if (hipStreamWaitEvent(stream, ev_[i], 0) != hipSuccess) return THANOS_ERR_HIP;
+    if (hipEventRecord(ctx_->ev[i], caller_) != hipSuccess) return THANOS_ERR_HIP;
+    if (hipStreamWaitEvent(stream, ctx_->ev[i], 0) != hipSuccess) return THANOS_ERR_HIP;
     open_ = true;
     last_rec_ = -1;
     return THANOS_OK;
@@ -78,31 +85,29 @@ class AuxStream {
   thanos_status record(int i) {
     if (inline_) return THANOS_OK;
     if (i < 0 || i >= nev_ - 1) return THANOS_ERR_HIP;
-    if (hipEventRecord(ev_[i], stream) != hipSuccess) return THANOS_ERR_HIP;
+    if (hipEventRecord(ctx_->ev[i], stream) != hipSuccess) return THANOS_ERR_HIP;
     last_rec_ = i;
     return THANOS_OK;
   }
   thanos_status join(int i) {
     if (inline_) return THANOS_OK;
     if (i < 0 || i >= nev_ - 1) return THANOS_ERR_HIP;
-    if (hipStreamWaitEvent(caller_, ev_[i], 0) != hipSuccess) return THANOS_ERR_HIP;
+    if (hipStreamWaitEvent(caller_, ctx_->ev[i], 0) != hipSuccess) return THANOS_ERR_HIP;
     if (i == last_rec_) open_ = false;
     return THANOS_OK;
   }
   ~AuxStream() {
-    if (inline_) return;
-    if (ok && open_ && hipEventRecord(ev_[nev_ - 1], stream) == hipSuccess)
-      (void)hipStreamWaitEvent(caller_, ev_[nev_ - 1], 0);
-    for (int i = 0; i < nev_; ++i) (void)hipEventDestroy(ev_[i]);
-    delete[] ev_;
-    if (stream) (void)hipStreamDestroy(stream);
+    if (inline_ || !ctx_) return;
+    if (open_ && hipEventRecord(ctx_->ev[nev_ - 1], stream) == hipSuccess)
+      (void)hipStreamWaitEvent(caller_, ctx_->ev[nev_ - 1], 0);
+    stream_ctx_release(ctx_);
   }
   AuxStream(const AuxStream&) = delete;
   AuxStream& operator=(const AuxStream&) = delete;
 
  private:
   hipStream_t caller_;
-  hipEvent_t* ev_ = nullptr;
+  StreamCtx* ctx_ = nullptr;
   int nev_ = 0;
   bool inline_;
   bool open_ = false;  // forked work that no join covers yet

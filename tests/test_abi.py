@@ -67,6 +67,35 @@ def test_host_side_argument_checks(L):
     assert t.thanos_prune_workspace_bytes(64, 256, p1) == 0           # p must be < 1
 
 
+def test_workspace_too_small_is_reported(L):
+    """THANOS_ERR_WORKSPACE comes from host-side checks: no pointer is dereferenced before it."""
+    import paper_2504_05346_amd as t
+    fake = ctypes.c_void_p(4096)          # non-NULL, 256-byte aligned, never touched
+    need = t.thanos_factor_workspace_bytes(256)
+    assert L.thanos_factor(fake, 256, 0.01, ctypes.c_void_p(8192), fake, fake, need - 1, fake,
+                           None) == 3
+    assert L.thanos_factor(fake, 256, 0.01, ctypes.c_void_p(8192), fake, None, need, fake,
+                           None) == 3
+    o = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=128,
+                    damping=0.01)
+    need = t.thanos_prune_workspace_bytes(64, 256, o)
+    assert need > 0
+    assert L.thanos_prune_layer(fake, t.THANOS_F16, 64, 256, fake, ctypes.byref(o), fake, None,
+                                fake, fake, need - 1, fake, None) == 3
+    assert t.thanos_status_string(3) == "workspace too small"
+    # U must not alias H; a given mask and outlier rows exclude each other
+    assert L.thanos_factor(fake, 256, 0.01, fake, fake, fake, 1 << 30, fake, None) == 1
+    om = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=128, damping=0.01,
+                     outlier_fraction=0.1)
+    om.mask_in = 4096
+    assert L.thanos_prune_layer(fake, t.THANOS_F16, 64, 256, fake, ctypes.byref(om), fake, None,
+                                fake, fake, 1 << 30, fake, None) == 2
+    # the structured mode puts rows in grid.y
+    so = t.PruneOpts(mode=t.THANOS_STRUCTURED, sparsity=0.3, n=0, m=0, block_size=128,
+                     damping=0.01)
+    assert t.thanos_prune_workspace_bytes(70000, 256, so) == 0
+
+
 def test_no_oracle_import_in_product():
     # the product path must never route through the CPU oracle
     pkg = os.path.join(ROOT, "paper_2504_05346_amd")
