@@ -46,7 +46,9 @@ typedef enum {
   THANOS_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels cover (see each call)  */
   THANOS_ERR_WORKSPACE = 3,   /* ws_bytes smaller than the matching *_workspace_bytes()         */
   THANOS_ERR_NOT_SPD = 4,     /* reserved for host-side callers that inspect info_dev           */
-  THANOS_ERR_HIP = 5          /* a HIP launch or runtime call failed                            */
+  THANOS_ERR_HIP = 5,         /* a HIP launch or runtime call failed                            */
+  THANOS_ERR_TOO_LARGE = 6    /* thanos_prune_layer_noalloc: the problem needs more workspace
+                                 than THANOS_NOALLOC_SCRATCH_BYTES                              */
 } thanos_status;
 
 typedef enum { THANOS_F32 = 0, THANOS_F16 = 1, THANOS_BF16 = 2 } thanos_dtype;
@@ -150,6 +152,30 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
                                  float* W_out, void* W_out_cast, uint8_t* mask_out, void* ws,
                                  size_t ws_bytes, int32_t* info_dev, void* stream);
 size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opts* opts /* host */);
+
+/*
+ * thanos_prune_layer for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * thanos_prune_layer, without ws / ws_bytes: the workspace is a static device array of
+ * THANOS_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.
+ * The call allocates nothing on the device or through HIP: no hipMalloc / hipFree, and no helper
+ * streams or events either (all kernels go to `stream` in one order; the overlap of
+ * thanos_prune_layer's helper streams is given up, the results are the same).  The first call on
+ * a device looks up that device's copy of the array (hipGetSymbolAddress, which may load the
+ * library's code on the device); the device current at the call must be the one `stream` and
+ * the buffers belong to.
+ * Limit: thanos_prune_workspace_bytes(c, b, opts) <= THANOS_NOALLOC_SCRATCH_BYTES, else
+ * THANOS_ERR_TOO_LARGE and nothing is enqueued (e.g. c = b = 1536 at B = 128 fits, with
+ * opts->factor_in c = b = 2048 does).
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents (the
+ * kernels initialise what they read): calls that overlap on one GPU -- from two threads, or on
+ * two streams without an ordering between them -- race.  Not re-entrant per device.
+ */
+#define THANOS_NOALLOC_SCRATCH_BYTES (64u << 20)
+thanos_status thanos_prune_layer_noalloc(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                         const float* H, const thanos_prune_opts* opts /* host */,
+                                         float* W_out, void* W_out_cast, uint8_t* mask_out,
+                                         int32_t* info_dev, void* stream);
 
 /* Static, NUL-terminated description of a status code (host pointer, never freed). */
 const char* thanos_status_string(thanos_status s);

@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     thanos_factor,
     thanos_factor_workspace_bytes,
     thanos_prune_layer,
+    thanos_prune_layer_noalloc,
+    THANOS_NOALLOC_SCRATCH_BYTES,
     thanos_prune_workspace_bytes,
     thanos_status_string,
 )

@@ -67,6 +67,9 @@ def lib() -> ctypes.CDLL:
     L.thanos_prune_layer.restype = ctypes.c_int
     L.thanos_prune_layer.argtypes = [vp, ctypes.c_int, i64, i64, vp, ctypes.POINTER(PruneOpts),
                                      vp, vp, vp, vp, sz, vp, vp]
+    L.thanos_prune_layer_noalloc.restype = ctypes.c_int
+    L.thanos_prune_layer_noalloc.argtypes = [vp, ctypes.c_int, i64, i64, vp,
+                                             ctypes.POINTER(PruneOpts), vp, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -148,3 +151,22 @@ def thanos_prune_layer(W_in: torch.Tensor, H: Optional[torch.Tensor], opts: Prun
                                   _ptr(mask_out), _ptr(ws), ws.numel() * ws.element_size(),
                                   _ptr(info), _stream(stream))
     _check(st, "thanos_prune_layer")
+
+
+THANOS_NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def thanos_prune_layer_noalloc(W_in: torch.Tensor, H: Optional[torch.Tensor], opts: PruneOpts,
+                               W_out: torch.Tensor, W_out_cast: Optional[torch.Tensor],
+                               mask_out: torch.Tensor, info: torch.Tensor, stream=None) -> None:
+    """thanos_prune_layer with the library's static device workspace (no ws argument)."""
+    c, b = W_in.shape
+    assert W_in.is_contiguous() and W_out.is_contiguous() and mask_out.is_contiguous()
+    assert W_out.dtype == torch.float32 and W_out.shape == (c, b)
+    assert mask_out.dtype == torch.uint8 and mask_out.shape == (c, b)
+    if W_out_cast is not None:
+        assert W_out_cast.dtype == W_in.dtype and W_out_cast.shape == (c, b)
+    st = lib().thanos_prune_layer_noalloc(_ptr(W_in), _dtype_code(W_in), c, b, _ptr(H),
+                                          ctypes.byref(opts), _ptr(W_out), _ptr(W_out_cast),
+                                          _ptr(mask_out), _ptr(info), _stream(stream))
+    _check(st, "thanos_prune_layer_noalloc")

@@ -81,6 +81,30 @@ void stream_ctx_release(StreamCtx* c) {
   pool.idle.push_back(c);
 }
 
+// Workspace of thanos_prune_layer_noalloc: one array per GPU, held from the moment the library's
+// code is loaded on that GPU until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it stands for differs from GPU to GPU.
+static __device__ __align__(256) unsigned char scratch[THANOS_NOALLOC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device, looked up once per device.
+static thanos_status scratch_of_current_device(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return THANOS_ERR_HIP;
+  std::lock_guard<std::mutex> guard(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return THANOS_ERR_HIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return THANOS_OK;
+}
+
+static bool dtype_ok(int d) { return d == THANOS_F32 || d == THANOS_F16 || d == THANOS_BF16; }
+
 // ---- counts derived from p and alpha ------------------------------------------------------
 // p and alpha are read as the decimal they print as: the shortest decimal string that converts
 // back to the same double (0.6 means 6/10, not the binary value just below it), and the counts
@@ -232,6 +256,7 @@ const char* thanos_status_string(thanos_status s) {
     case THANOS_ERR_WORKSPACE: return "workspace too small";
     case THANOS_ERR_NOT_SPD: return "matrix not positive definite";
     case THANOS_ERR_HIP: return "HIP runtime error";
+    case THANOS_ERR_TOO_LARGE: return "problem exceeds the static scratch of the no-allocation entry point";
   }
   return "unknown status";
 }
@@ -334,6 +359,22 @@ thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, 
   if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return THANOS_ERR_INVALID_ARG;
   return prune_with_workspace(W_in, wdt, c, b, H, opts, W_out, W_out_cast, mask_out, ws, info_dev,
                               reinterpret_cast<hipStream_t>(stream), false);
+}
+
+thanos_status thanos_prune_layer_noalloc(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                                         const float* H, const thanos_prune_opts* opts,
+                                         float* W_out, void* W_out_cast, uint8_t* mask_out,
+                                         int32_t* info_dev, void* stream) {
+  thanos_status st = check_prune_args(W_in, wdt, c, b, H, opts, W_out, mask_out, info_dev);
+  if (st != THANOS_OK) return st;
+  if (thanos_prune_workspace_bytes(c, b, opts) > (size_t)THANOS_NOALLOC_SCRATCH_BYTES)
+    return THANOS_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  st = scratch_of_current_device(&ws);
+  if (st != THANOS_OK) return st;
+  // single stream: no helper streams or events are created; the kernels run in enqueue order
+  return prune_with_workspace(W_in, wdt, c, b, H, opts, W_out, W_out_cast, mask_out, ws, info_dev,
+                              reinterpret_cast<hipStream_t>(stream), true);
 }
 
 }  // extern "C"

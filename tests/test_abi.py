@@ -34,8 +34,8 @@ def test_exports_every_declared_symbol(L):
 
 def test_status_strings(L):
     import paper_2504_05346_amd as t
-    seen = {t.thanos_status_string(s) for s in range(6)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {t.thanos_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
     assert t.thanos_status_string(99) == "unknown status"
 
 
@@ -94,6 +94,11 @@ def test_workspace_too_small_is_reported(L):
     so = t.PruneOpts(mode=t.THANOS_STRUCTURED, sparsity=0.3, n=0, m=0, block_size=128,
                      damping=0.01)
     assert t.thanos_prune_workspace_bytes(70000, 256, so) == 0
+    # the entry point without a workspace argument rejects what its static array cannot hold
+    big = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=128, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(4096, 4096, big) > t.THANOS_NOALLOC_SCRATCH_BYTES
+    assert L.thanos_prune_layer_noalloc(fake, t.THANOS_F16, 4096, 4096, fake, ctypes.byref(big),
+                                        fake, None, fake, fake, None) == 6
 
 
 def test_no_oracle_import_in_product():
