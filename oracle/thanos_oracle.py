@@ -344,7 +344,8 @@ def inverse_factor(Hd: np.ndarray) -> np.ndarray:
 
     Then inv(Hd[j:, j:]) = U[j:, j:]^T U[j:, j:] for every j, which is the
     matrix Alg. 1 re-computes after each block ("H <- 2(XX^T)_{j2:b, j2:b}").
-    tests/test_oracle_fast.py checks that identity against np.linalg.inv.
+    tests/test_oracle_steps.py (test_inverse_factor_gives_every_residual_inverse) checks that
+    identity against np.linalg.inv of every trailing sub-matrix.
     """
     Hinv = sla.cho_solve(sla.cho_factor(Hd, lower=True), np.eye(Hd.shape[0]))
     Hinv = 0.5 * (Hinv + Hinv.T)

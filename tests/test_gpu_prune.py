@@ -54,6 +54,11 @@ def test_cfg1_unstructured(rho):
                                              return_margins=True)
     assert margins.min() > 5e-6, "seed has a near-tie; pick another"
     _check(W, H32, Wg, Mg, Wo, Mo)
+    # the same decisions when the oracle ranks the plain float64 metric instead of the one rounded
+    # to float32 like the kernel's: with margins > 5e-6 a rounding of ~2e-7 decides nothing
+    _, Mo64 = orc.prune_unstructured(W, H32.astype(np.float64), 0.5, 128, 0.01,
+                                     metric_dtype=np.float64)
+    np.testing.assert_array_equal(Mg, Mo64)
     Wm, _ = orc.magnitude_prune(W, p=0.5)
     H = H32.astype(np.float64)
     assert orc.reconstruction_error(W, Wg.astype(np.float64), H) <= orc.reconstruction_error(W, Wm, H)
@@ -82,6 +87,13 @@ def test_cfg1_nm(n, m, rho):
     np.testing.assert_array_equal(Mg[ok], Mo[ok])
     assert _rel(Wg[ok], Wo[ok]) < 1e-3
     _check(W, H32, Wg, Mg, Wo, Mo, exact_mask=False)
+    # oracle ranking the plain float64 metric: same masks wherever its own margins are clear
+    _, Mo64, mg64 = orc.prune_nm(W, H32.astype(np.float64), n, m, 128, 0.01,
+                                 metric_dtype=np.float64, return_margins=True)
+    clear = np.all(mg64 > 1e-5, axis=1)
+    assert clear.mean() > 0.95
+    np.testing.assert_array_equal(Mg[clear & np.isin(np.arange(512), ok)],
+                                  Mo64[clear & np.isin(np.arange(512), ok)])
 
 
 # --------------------------------------------------------------------------- ragged shapes
@@ -341,6 +353,9 @@ def test_threshold_jumps_between_blocks():
     per_block = Mo.reshape(96, 4, 128).sum(axis=(0, 2))
     assert per_block[2] == 96 * 128 and per_block[1] < 96
     _check(W, H32, Wg, Mg, Wo, Mo)
+    _, Mo64 = orc.prune_unstructured(W, H32.astype(np.float64), 0.5, 128, 0.01,
+                                     metric_dtype=np.float64)
+    np.testing.assert_array_equal(Mg, Mo64)
 
 
 def test_sparsity_edge_values():

@@ -101,6 +101,87 @@ def test_columns_left_of_a_block_are_frozen_and_blocks_see_updated_weights():
     assert np.any(M[:, 8:] != M_static[:, 8:])
 
 
+def test_unstructured_later_blocks_rank_the_updated_weights_with_the_reduced_budget():
+    """Alg. 1: the global residual mask of block j+1 is psi_X of the weights AFTER block j's row
+    updates, with r reduced by ||M||_F^2 of block j.  Replayed by hand for the second and third
+    block (psi, one inverse of the residual Hessian and row_update per row, nothing else)."""
+    W, X, H = _layer(6, c=8, b=32, T=200)
+    p, B, damp = 0.5, 8, 0.01
+    Wh, M = orc.prune_unstructured(W, H, p, B, damp)
+    xn2 = np.diag(H)
+    Hd = orc.damped(H, damp)
+    Wcur = W.astype(np.float64).copy()
+    r = (8 * 32) // 2
+    differs_from_static = False
+    for j1 in (0, 8, 16):
+        Mb = orc.psi(Wcur[:, j1:], xn2[j1:], r)[:, :B]
+        np.testing.assert_array_equal(M[:, j1:j1 + B], Mb)
+        if j1 > 0:
+            # the same budget on the INPUT weights gives another mask: the ranking did see the updates
+            Mstatic = orc.psi(W[:, j1:].astype(np.float64), xn2[j1:], r)[:, :B]
+            differs_from_static |= bool(np.any(Mstatic != Mb))
+        Hinv = np.linalg.inv(Hd[j1:, j1:])
+        for i in range(8):
+            Wcur[i, j1:] = orc.row_update(Wcur[i, j1:], Hinv, orc.phi(Mb[i]))
+        r -= int(Mb.sum())
+        np.testing.assert_allclose(Wh[:, j1:j1 + B], Wcur[:, j1:j1 + B], rtol=1e-12, atol=0)
+    assert differs_from_static
+    # and a budget that was not reduced would overshoot: the count is exact
+    assert int(M.sum()) == (8 * 32) // 2
+
+
+# ------------------------------------------------------------------ decision margins
+def test_global_margin_by_hand():
+    """Relative gap between the r-th and (r+1)-th smallest metric of a residual, on a 3 x 8
+    example small enough to sort by eye: metric = |W| * sqrt(4) = 2 |W|."""
+    W = np.array([[1, -2, 3, -4, 5, -6, 7, -8],
+                  [9, 10, -11, 12, 13, -14, 15, 16],
+                  [-17, 18, 19, 20, -21, 22, 23, -24]], dtype=np.float64)
+    xn2 = np.full(8, 4.0)
+    for dt in (np.float32, np.float64):
+        # sorted metrics 2, 4, ..., 48: the 5th is 10, the 6th is 12
+        assert orc._global_margin(W, xn2, 5, dt) == pytest.approx((12 - 10) / 12, rel=1e-6)
+        assert orc._global_margin(W, xn2, 23, dt) == pytest.approx((48 - 46) / 48, rel=1e-6)
+        assert orc._global_margin(W, xn2, 0, dt) == float("inf")     # nothing selected
+        assert orc._global_margin(W, xn2, 24, dt) == float("inf")    # everything selected
+        Wt = W.copy()
+        Wt[1, 0] = -5.0                       # planted tie at the cut: 2, 4, 6, 8, 10 | 10, 12
+        assert orc._global_margin(Wt, xn2, 5, dt) == 0.0
+        assert orc._global_margin(Wt, xn2, 4, dt) == pytest.approx((10 - 8) / 10, rel=1e-6)
+        Wg = W.copy()
+        Wg[0, 5] = 100.0                      # planted gap: 2, ..., 10 | 14, ... (12 is gone)
+        assert orc._global_margin(Wg, xn2, 5, dt) == pytest.approx((14 - 10) / 14, rel=1e-6)
+    # the sweep reports the margin of the decision it takes: block 0 on the input weights
+    _, _, mg = orc.prune_unstructured(W, np.diag(xn2), 5 / 24, 4, 0.0, return_margins=True)
+    assert mg[0] == pytest.approx(1 / 6, rel=1e-6)
+
+
+def test_group_margins_by_hand():
+    """Per row and group of m: relative gap between the n-th and (n+1)-th smallest metric."""
+    W = np.array([[1, -2, 3, -4, 8, 6, -7, 5],
+                  [3, 1, 1, 2, 1, 2, -2, 3],
+                  [10, 0, 0, 20, 1, 1, 1, 1]], dtype=np.float64)
+    xn2 = np.full(8, 4.0)
+    for dt in (np.float32, np.float64):
+        g = orc._group_margins(W, xn2, 2, 4, dt)
+        assert g.shape == (3, 2)
+        want = np.array([[(6 - 4) / 6, (14 - 12) / 14],      # 2,4|6,8 ; 10,12|14,16
+                         [(4 - 2) / 4, 0.0],                 # 2,2|4,6 ; 2,4|4,6: tie at the cut
+                         [1.0, 0.0]])                        # 0,0|20,40 ; all equal
+        np.testing.assert_allclose(g, want, rtol=1e-6, atol=0)
+        g1 = orc._group_margins(W, xn2, 1, 4, dt)
+        np.testing.assert_allclose(g1[0], [(4 - 2) / 4, (12 - 10) / 12], rtol=1e-6)
+        assert g1[1, 0] == 0.0 and g1[2, 0] == 0.0            # 2|2 ; 0|0 -> tiny denominator, gap 0
+    # a decision flips exactly when a perturbation exceeds the margin: scale the 2nd smallest
+    # of group (0, 0) past the 3rd and the n:m mask changes, just below it and it does not
+    base = orc.nm_mask(W[:1, :4], xn2[:4], 2, 4)
+    below, above = W[:1, :4].copy(), W[:1, :4].copy()
+    below[0, 1] *= 1 + 0.9 * 0.5              # 4 -> 5.8 < 6: margin relative to the kept value is
+    above[0, 1] *= 1 + 1.1 * 0.5              # (6-4)/6, i.e. 0.5 relative to the removed one
+    np.testing.assert_array_equal(orc.nm_mask(below, xn2[:4], 2, 4), base)
+    assert np.any(orc.nm_mask(above, xn2[:4], 2, 4) != base)
+
+
 # ------------------------------------------------------------------ invariances
 def test_hessian_scale_invariance():
     W, X, H = _layer(7)
