@@ -53,6 +53,11 @@ def parse_args():
     ap.add_argument("--damping", type=float, default=0.01)
     ap.add_argument("--outlier-fraction", type=float, default=0.0,
                     help="alpha of the n:m algorithm: share of rows (largest loss) left dense")
+    ap.add_argument("--rho", type=float, default=0.0,
+                    help="correlated calibration channels (0 = independent, as configured)")
+    ap.add_argument("--outlier-channels", action="store_true",
+                    help="heavy-tailed activations: 0.5 %% of the channels scaled x20-100")
+    ap.add_argument("--w-std", type=float, default=0.02)
     ap.add_argument("--chunks", type=int, default=1,
                     help="number of thanos_hessian_accumulate calls the tokens are split into")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -64,22 +69,14 @@ def parse_args():
 
 
 def make_inputs(args, torch):
-    """Seeded synthetic layer on the device: W ~ N(0, 0.02^2) fp16, X[t, j] = s_j * g, fp16."""
-    from synth import LayerSpec, channel_scales
-    spec = LayerSpec("bench", c=args.c, b=args.b, tokens=args.tokens, dtype="f16", seed=0)
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(1234)
-    W = (torch.randn((args.c, args.b), generator=gen, device="cuda", dtype=torch.float32)
-         * spec.w_std).to(torch.float16)
-    s = torch.from_numpy(channel_scales(spec)).to(device="cuda", dtype=torch.float32)
-    X = torch.empty((args.tokens, args.b), dtype=torch.float16, device="cuda")
-    step = 8192
-    for t0 in range(0, args.tokens, step):
-        n = min(step, args.tokens - t0)
-        g = torch.randn((n, args.b), generator=gen, device="cuda", dtype=torch.float32)
-        X[t0:t0 + n] = (g * s).to(torch.float16)
-    torch.cuda.synchronize()
-    return W, X
+    """Seeded synthetic layer on the device: W ~ N(0, w_std^2) fp16, X[t, j] = s_j * g, fp16
+    (synth.make_layer_on_device; --rho / --outlier-channels select the correlated and the
+    heavy-tailed variant of the recipe)."""
+    from synth import LayerSpec, make_layer_on_device
+    spec = LayerSpec("bench", c=args.c, b=args.b, tokens=args.tokens, dtype="f16", seed=0,
+                     rho=getattr(args, "rho", 0.0), outliers=getattr(args, "outlier_channels", False),
+                     w_std=getattr(args, "w_std", 0.02))
+    return make_layer_on_device(spec, torch)
 
 
 def cpu_baseline(args, W, X, torch):

@@ -82,6 +82,13 @@ typedef struct {
                               ties by row index.  0 = prune every row.  THANOS_NM and
                               THANOS_STRUCTURED; needs H (undamped) even when factor_in is
                               given.                                                            */
+  float* threshold_out;    /* optional, THANOS_UNSTRUCTURED without mask_in: ceil(b/B) floats
+                              (device); entry j receives tau_j, the largest metric
+                              |W_ik| * sqrt(xnorm2_k) that the global residual mask of block j
+                              (psi_X over W[:, jB:b], Sec. 4.4) selects: entries below tau_j are
+                              removed, entries equal to it in (row, column) order while the
+                              budget r lasts.  -1 where nothing was left to remove.  NULL = not
+                              reported.                                                         */
 } thanos_prune_opts;
 
 /*

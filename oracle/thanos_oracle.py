@@ -356,10 +356,14 @@ def prune_fast(W: np.ndarray, H: np.ndarray, *, mode: str, p=None, n: int = 0, m
                B: int, damp: float, metric_dtype=np.float32,
                mask_in: Optional[np.ndarray] = None,
                U: Optional[np.ndarray] = None, alpha=0,
-               rows: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+               rows: Optional[np.ndarray] = None,
+               on_block=None) -> Tuple[np.ndarray, np.ndarray]:
     """Same sweeps as prune_unstructured / prune_nm, but every residual inverse is
-    read off one factor U (see inverse_factor) and the row loop is vectorised per
-    group of rows that share a count s.  mask_in (c x b) forces the mask.
+    read off one factor U (see inverse_factor).  mask_in (c x b) forces the mask.
+
+    on_block(j1, j2, W_current), if given, is called at the start of every block, before its
+    mask is chosen, with the weights as they stand (read-only view for tests that check the
+    decisions of a block against the weights the block actually saw); it changes nothing.
     """
     W = np.array(W, dtype=np.float64, copy=True)
     c, b = W.shape
@@ -373,6 +377,8 @@ def prune_fast(W: np.ndarray, H: np.ndarray, *, mode: str, p=None, n: int = 0, m
     for j1, j2 in _blocks(b, B):
         Ubb = U[j1:j2, j1:j2]
         Rows = Ubb.T @ U[j1:j2, j1:]          # first (j2-j1) rows of the residual inverse
+        if on_block is not None:
+            on_block(j1, j2, W)
         if mask_in is not None:
             M = np.asarray(mask_in[:, j1:j2], dtype=np.uint8)
         elif mode == "unstructured":

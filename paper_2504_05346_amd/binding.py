@@ -37,6 +37,7 @@ class PruneOpts(ctypes.Structure):
         ("factor_in", ctypes.c_void_p),
         ("xnorm2_in", ctypes.c_void_p),
         ("outlier_fraction", ctypes.c_double),
+        ("threshold_out", ctypes.c_void_p),
     ]
 
 

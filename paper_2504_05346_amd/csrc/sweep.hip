@@ -364,11 +364,13 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
                                                   SelState* __restrict__ st,
                                                   const unsigned int* __restrict__ hist_in,
                                                   const int* __restrict__ row_cand,
-                                                  int* __restrict__ row_eq, int vec) {
+                                                  int* __restrict__ row_eq, int vec,
+                                                  float* __restrict__ tau_out) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave;
   if (st->none) {  // uniform
     if (i < c && lane == 0) row_eq[i] = 0;
+    if (tau_out && blockIdx.x == 0 && threadIdx.x == 0) *tau_out = -1.f;
     return;
   }
   const int shift = st->shift;
@@ -379,6 +381,7 @@ __global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, i
   const bool all = rank_eq == (long long)r.count;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     st->tau = tau;
+    if (tau_out) *tau_out = __uint_as_float(tau);
     st->need_eq = all ? (1ll << 62) : rank_eq;
     st->ties_all = all ? 1 : 0;
     const unsigned int p28 = tau >> 4;
@@ -1803,7 +1806,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       hipLaunchKernelGGL(k_sel_hist<2>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
                          hist_b, hist_c, w.row_cand, sel_vec);
       hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         hist_c, w.row_cand, w.row_eq, sel_vec);
+                         hist_c, w.row_cand, w.row_eq, sel_vec,
+                         o->threshold_out ? o->threshold_out + blk : nullptr);
       hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c, w.st);
       THANOS_LAUNCH_CHECK();
     }

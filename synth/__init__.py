@@ -13,3 +13,4 @@ from .inputs import (  # noqa: F401
     make_calibration,
     layer_spec,
 )
+from .device import make_layer_on_device  # noqa: F401,E402
