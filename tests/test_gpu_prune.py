@@ -83,6 +83,13 @@ def test_cfg1_nm(n, m, rho):
         for i, j in first.items():
             assert mg[i, j] < 1e-4, (i, j, mg[i, j])
         assert len(bad_rows) <= 2
+    print(f"  rows whose mask differs from the free-running oracle: {len(bad_rows)}", flush=True)
+    # every decision of every block (not only the first differing one of a row) against the
+    # oracle's decision on the weights that block saw; W_hat and reconstruction error per row
+    from tests.fullsize_util import check_nm_rows
+    Hd64 = H32.astype(np.float64)
+    check_nm_rows(W, Hd64, orc.inverse_factor(orc.damped(Hd64, 0.01)), Wg.astype(np.float64), Mg,
+                  n, m, 128, 0.01, f"cfg1 {n}:{m} rho={rho}")
     ok = np.setdiff1d(np.arange(512), bad_rows)
     np.testing.assert_array_equal(Mg[ok], Mo[ok])
     assert _rel(Wg[ok], Wo[ok]) < 1e-3

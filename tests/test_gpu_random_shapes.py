@@ -44,6 +44,7 @@ def _draw(rng):
 def test_random_cases(case_seed):
     from tests.gpu_util import gpu_prune
     rng = np.random.default_rng(case_seed)
+    near_tie_skips = 0
     for it in range(12):
         mode, c, b, B, n, m, p, alpha, dtype, rho, seed = _draw(rng)
         if mode == "structured" and p / (1.0 - alpha) >= 1.0:
@@ -74,8 +75,25 @@ def test_random_cases(case_seed):
             Wg, Mg, info = gpu_prune(W, H32, mode="structured", p=p, alpha=alpha)
             Wt, Mo = orc.prune_structured(W, H, p, alpha, 0.01)
             assert Mg.sum() == Mo.sum()
-            if not np.array_equal(Mg, Mo):          # a near-tie in the column or row ranking
+            if not np.array_equal(Mg, Mo):
+                # accepted only if the oracle's own ranking has a near-tie at one of its two
+                # cuts (column losses at s, row losses at the outlier cut); counted, not hidden
+                rows_o = orc.pruned_rows(W.astype(np.float64), H, alpha)
+                v = np.sort(orc.column_losses(W, np.diag(H), rows_o))
+                s_cols = orc.num_columns_to_remove(p, alpha, b)
+                gaps = []
+                if 0 < s_cols < b:
+                    gaps.append((v[s_cols] - v[s_cols - 1]) / max(v[s_cols], 1e-300))
+                n_out = orc.num_outlier_rows(alpha, c)
+                if 0 < n_out < c:
+                    h = np.sort(orc.row_losses(W, H))
+                    gaps.append((h[c - n_out] - h[c - n_out - 1]) / max(h[c - n_out], 1e-300))
+                assert gaps and min(gaps) < 1e-3, ("structured masks differ without a near-tie",
+                                                   gaps)
+                near_tie_skips += 1
+                print(f"  structured ranking near-tie (gaps {gaps}): W_hat not compared", flush=True)
                 continue
         assert info == 0
         assert np.all(Wg[Mg == 1] == 0.0)
         assert np.linalg.norm(Wg - Wt) <= 1e-3 * max(np.linalg.norm(Wt), 1e-30)
+    assert near_tie_skips <= 1
