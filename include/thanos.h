@@ -54,6 +54,20 @@ typedef enum {
 typedef enum { THANOS_F32 = 0, THANOS_F16 = 1, THANOS_BF16 = 2 } thanos_dtype;
 typedef enum { THANOS_UNSTRUCTURED = 0, THANOS_NM = 1, THANOS_STRUCTURED = 2 } thanos_mode;
 
+/* Phases of thanos_prune_layer as reported through thanos_prune_opts.phase_ms_out. */
+enum {
+  THANOS_PHASE_PREP = 0,     /* weights to fp32, sqrt(xnorm2), outlier rows, block rows P_k of
+                                the residual inverses                                          */
+  THANOS_PHASE_FACTOR = 1,   /* damped factorisation (0 when factor_in is given)               */
+  THANOS_PHASE_MASK = 2,     /* unstructured: the selection chain (threshold of the global
+                                residual mask); n:m and given masks: 0, the choice is made
+                                inside the solve kernels                                       */
+  THANOS_PHASE_SOLVE = 3,    /* per-row systems lambda R_hat = u (with the block mask)         */
+  THANOS_PHASE_UPDATE = 4,   /* trailing update W[:, j1:] -= Lambda P_k                        */
+  THANOS_PHASE_FINALISE = 5, /* cast copy                                                      */
+  THANOS_N_PHASES = 6
+};
+
 /* Options of the block sweep (host struct, read during the call only). */
 typedef struct {
   int32_t mode;       /* THANOS_UNSTRUCTURED (Alg. 1), THANOS_NM (n:m algorithm, App. G.4.4) or
@@ -89,6 +103,12 @@ typedef struct {
                               removed, entries equal to it in (row, column) order while the
                               budget r lasts.  -1 where nothing was left to remove.  NULL = not
                               reported.                                                         */
+  float* phase_ms_out;     /* optional HOST pointer to THANOS_N_PHASES floats.  Diagnostic mode
+                              (not THANOS_STRUCTURED): the kernels of the call run one after the
+                              other on `stream` (no helper streams, hence no overlap), timing
+                              events are recorded between the phases, the call WAITS for the
+                              stream and writes the milliseconds of each phase.  Same results
+                              as a normal call.  NULL = normal asynchronous call.               */
 } thanos_prune_opts;
 
 /*
@@ -171,6 +191,7 @@ size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opt
  * a device looks up that device's copy of the array (hipGetSymbolAddress, which may load the
  * library's code on the device); the device current at the call must be the one `stream` and
  * the buffers belong to.
+ * opts->phase_ms_out must be NULL (the diagnostic mode creates events): UNSUPPORTED otherwise.
  * Limit: thanos_prune_workspace_bytes(c, b, opts) <= THANOS_NOALLOC_SCRATCH_BYTES, else
  * THANOS_ERR_TOO_LARGE and nothing is enqueued (e.g. c = b = 1536 at B = 128 fits, with
  * opts->factor_in c = b = 2048 does).

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     ThanosError,
     PruneOpts,
     THANOS_F32, THANOS_F16, THANOS_BF16,
-    THANOS_UNSTRUCTURED, THANOS_NM, THANOS_STRUCTURED,
+    THANOS_UNSTRUCTURED, THANOS_NM, THANOS_STRUCTURED, THANOS_PHASES,
     thanos_hessian_accumulate,
     thanos_factor,
     thanos_factor_workspace_bytes,

@@ -15,6 +15,7 @@ import torch  # noqa: F401  (imported first so that the HIP runtime torch ships 
 
 THANOS_F32, THANOS_F16, THANOS_BF16 = 0, 1, 2
 THANOS_UNSTRUCTURED, THANOS_NM, THANOS_STRUCTURED = 0, 1, 2
+THANOS_PHASES = ("prep", "factor", "mask", "solve", "update", "finalise")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(_HERE, "libthanos.so")
@@ -38,6 +39,7 @@ class PruneOpts(ctypes.Structure):
         ("xnorm2_in", ctypes.c_void_p),
         ("outlier_fraction", ctypes.c_double),
         ("threshold_out", ctypes.c_void_p),
+        ("phase_ms_out", ctypes.c_void_p),
     ]
 
 

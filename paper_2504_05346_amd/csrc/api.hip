@@ -12,7 +12,8 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers);
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
-                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream);
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
+                    PhaseTimer* pt);
 size_t structured_workspace_bytes(int64_t c, int64_t b);
 thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                          const float* H, float damping, long long s_cols, long long n_out,
@@ -319,11 +320,24 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
                                           float* W_out, void* W_out_cast, uint8_t* mask_out,
                                           void* ws, int32_t* info_dev, hipStream_t s,
                                           bool single_stream) {
-  if (opts->mode == THANOS_STRUCTURED)
+  if (opts->mode == THANOS_STRUCTURED) {
+    if (opts->phase_ms_out) return THANOS_ERR_UNSUPPORTED;
     return structured(s, W_in, wdt, c, b, H, opts->damping,
                       num_columns_to_remove(opts->sparsity, opts->outlier_fraction, b),
                       num_outlier_rows(opts->outlier_fraction, c), W_out, W_out_cast, mask_out, ws,
                       info_dev, single_stream);
+  }
+  // diagnostic mode: phases timed with events, kernels serialised on the one stream
+  PhaseTimer* pt = nullptr;
+  struct TimerOwner {
+    PhaseTimer* t = nullptr;
+    ~TimerOwner() { delete t; }
+  } owner;
+  if (opts->phase_ms_out) {
+    owner.t = pt = new PhaseTimer(s);
+    single_stream = true;
+  }
+  phase_mark(pt, THANOS_PHASE_FACTOR);
   char* p = reinterpret_cast<char*>(ws);
   void* sweep_ws = p;
   p += sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
@@ -345,8 +359,14 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
   const long long r_total =
       (opts->mode == THANOS_UNSTRUCTURED) ? num_to_remove(opts->sparsity, c, b) : 0;
   const long long n_out = num_outlier_rows(opts->outlier_fraction, c);
-  return sweep(s, W_in, wdt, c, b, H, U, xn2, opts, r_total, n_out, W_out, W_out_cast, mask_out,
-               sweep_ws, info_dev, single_stream);
+  phase_mark(pt, THANOS_PHASE_PREP);
+  thanos_status st = sweep(s, W_in, wdt, c, b, H, U, xn2, opts, r_total, n_out, W_out, W_out_cast,
+                           mask_out, sweep_ws, info_dev, single_stream, pt);
+  if (pt) {
+    const thanos_status tc = pt->collect(opts->phase_ms_out);
+    if (st == THANOS_OK) st = tc;
+  }
+  return st;
 }
 
 thanos_status thanos_prune_layer(const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
@@ -367,6 +387,7 @@ thanos_status thanos_prune_layer_noalloc(const void* W_in, thanos_dtype wdt, int
                                          int32_t* info_dev, void* stream) {
   thanos_status st = check_prune_args(W_in, wdt, c, b, H, opts, W_out, mask_out, info_dev);
   if (st != THANOS_OK) return st;
+  if (opts->phase_ms_out) return THANOS_ERR_UNSUPPORTED;  // the diagnostic mode creates events
   if (thanos_prune_workspace_bytes(c, b, opts) > (size_t)THANOS_NOALLOC_SCRATCH_BYTES)
     return THANOS_ERR_TOO_LARGE;
   void* ws = nullptr;

@@ -113,6 +113,47 @@ class AuxStream {
   bool open_ = false;  // forked work that no join covers yet
   int last_rec_ = -1;  // event of the last record since the last fork
 };
+// Diagnostic phase timing of one call: mark(p) records a timing event on the stream and says
+// "what follows belongs to phase p"; collect() waits for the stream and adds the time between
+// consecutive marks to the phase of the earlier one.  A null pointer or a disabled timer costs
+// nothing.  Only meaningful when all kernels of the call run on the one stream.
+class PhaseTimer {
+ public:
+  explicit PhaseTimer(hipStream_t s) : s_(s) {}
+  void mark(int phase) {
+    if (n_ >= kMax - (phase < 0 ? 0 : 1)) return;  // the last slot is kept for the closing mark
+    if (hipEventCreate(&ev_[n_]) != hipSuccess) return;
+    (void)hipEventRecord(ev_[n_], s_);
+    ph_[n_++] = phase;
+  }
+  thanos_status collect(float* out) {  // THANOS_N_PHASES floats
+    mark(-1);
+    thanos_status st = hipStreamSynchronize(s_) == hipSuccess ? THANOS_OK : THANOS_ERR_HIP;
+    for (int p = 0; p < THANOS_N_PHASES; ++p) out[p] = 0.f;
+    for (int i = 0; i + 1 < n_ && st == THANOS_OK; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev_[i], ev_[i + 1]) != hipSuccess) st = THANOS_ERR_HIP;
+      else if (ph_[i] >= 0 && ph_[i] < THANOS_N_PHASES) out[ph_[i]] += ms;
+    }
+    return st;
+  }
+  ~PhaseTimer() {
+    for (int i = 0; i < n_; ++i) (void)hipEventDestroy(ev_[i]);
+  }
+  PhaseTimer(const PhaseTimer&) = delete;
+  PhaseTimer& operator=(const PhaseTimer&) = delete;
+
+ private:
+  static constexpr int kMax = 4096;
+  hipStream_t s_;
+  hipEvent_t ev_[kMax];
+  int ph_[kMax];
+  int n_ = 0;
+};
+static inline void phase_mark(PhaseTimer* t, int phase) {
+  if (t) t->mark(phase);
+}
+
 #define THANOS_CHECK(expr)                 \
   do {                                     \
     thanos_status st_ = (expr);            \

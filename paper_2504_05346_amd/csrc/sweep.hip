@@ -1722,7 +1722,8 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
-                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream) {
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
+                    PhaseTimer* pt) {
   const int B = o->block_size;
   const bool outliers = n_out > 0;
   SweepWs w = carve_ws(ws, c, b, B, outliers);
@@ -1789,6 +1790,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     const int64_t loff = (super == 1) ? 0 : (j1 - sb_start);
     float* lam_sb = w.Lam + (sbi & 1) * (int64_t)c * ldl;
     if (unstructured) {
+      phase_mark(pt, THANOS_PHASE_MASK);
       // 16-byte loads need W + i*b + j1 and sx + j1 aligned (W, sx come 256-byte aligned)
       const int sel_vec = (b % 4 == 0 && j1 % 4 == 0 &&
                            reinterpret_cast<uintptr_t>(W) % 16 == 0) ? 1 : 0;
@@ -1811,6 +1813,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c, w.st);
       THANOS_LAUNCH_CHECK();
     }
+    phase_mark(pt, THANOS_PHASE_SOLVE);
     SolveArgs sa;
     sa.W = W;
     sa.P = w.P;
@@ -1843,6 +1846,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     }
     THANOS_LAUNCH_CHECK();
 
+    phase_mark(pt, THANOS_PHASE_UPDATE);
     {  // this block's update, up to the end of its super-block
       dim3 grid((unsigned)ceil_div(sb_end - j1, kTN), (unsigned)ceil_div(c, kTM));
       const bool feed = unstructured && j1 + bw < b;  // a next block exists: count its window
@@ -1882,6 +1886,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   }
   if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
 
+  phase_mark(pt, THANOS_PHASE_FINALISE);
   if (W_cast) {
     if (wdt == THANOS_F32)
       hipLaunchKernelGGL(k_from_f32<float>, dim3(nblk), dim3(256), 0, s, W, (float*)W_cast, n);

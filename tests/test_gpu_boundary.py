@@ -138,3 +138,35 @@ def test_outlier_row_count_is_ceil_of_the_decimal_product(alpha, c):
     assert int(info.item()) == 0
     untouched = int((M.sum(dim=1) == 0).sum().item())
     assert untouched == orc.num_outlier_rows(alpha, c)
+
+
+@pytest.mark.parametrize("mode", ["nm", "unstructured"])
+def test_diagnostic_phase_timing_gives_the_same_result(mode):
+    """opts.phase_ms_out: kernels serialised on the stream and timed per phase by the library;
+    masks and W_hat are those of the normal call, every phase that runs reports a time."""
+    import ctypes
+    import torch
+    import paper_2504_05346_amd as th
+    W, X = _layer(256, 1280, 2048, seed=23, dtype="f16")
+    Wd = torch.from_numpy(W).cuda()
+    H = torch.from_numpy(orc.hessian(X).astype(np.float32)).cuda()
+    o = th.PruneOpts(mode=th.THANOS_NM if mode == "nm" else th.THANOS_UNSTRUCTURED, sparsity=0.5,
+                     n=2, m=4, block_size=128, damping=0.01)
+    Wo, Wc, M, info, _ = _prune_torch(Wd, H, o)
+    torch.cuda.synchronize()
+    buf = (ctypes.c_float * len(th.THANOS_PHASES))(*([-1.0] * len(th.THANOS_PHASES)))
+    o.phase_ms_out = ctypes.addressof(buf)
+    Wo2, Wc2, M2, info2, _ = _prune_torch(Wd, H, o)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0 and int(info2.item()) == 0
+    assert torch.equal(M, M2) and torch.equal(Wo, Wo2) and torch.equal(Wc, Wc2)
+    ph = dict(zip(th.THANOS_PHASES, list(buf)))
+    print(f"phases {mode}: {ph}", flush=True)
+    for k in ("prep", "factor", "solve", "update", "finalise"):
+        assert 0.0 < ph[k] < 1000.0, (k, ph)
+    assert (ph["mask"] > 0.0) == (mode == "unstructured")
+    # the no-allocation entry point refuses the diagnostic mode (it would create events)
+    st = th.lib().thanos_prune_layer_noalloc(Wd.data_ptr(), th.THANOS_F16, 256, 1280, H.data_ptr(),
+                                             ctypes.byref(o), Wo2.data_ptr(), None, M2.data_ptr(),
+                                             info2.data_ptr(), None)
+    assert st == 2
