@@ -80,10 +80,13 @@ typedef struct {
                          means 6/10.  Ignored for THANOS_NM.                                  */
   int32_t n, m;       /* THANOS_NM: n of every m consecutive weights of a row are removed;
                          0 < n < m <= 16, m divides block_size and b                          */
-  int32_t block_size; /* B: columns pruned per sweep step, B >= 1.  A row's system of one block
-                         must not exceed 256 unknowns: B <= 256 in general; THANOS_NM without
-                         mask_in also takes B <= 512 with B*n/m <= 256 (2:4 and 4:8 at the
-                         B = 512 of the paper's experiments).  The last block may be narrower. */
+  int32_t block_size; /* B: columns pruned per sweep step, 1 <= B <= 4096.  A row's system of
+                         one block must not exceed 2048 unknowns: B <= 2048 in general;
+                         THANOS_NM without mask_in takes B <= 4096 with B*n/m <= 2048 (the whole
+                         range of the block-size ablation in the Experiments section).  Systems
+                         of up to 256 unknowns in blocks of up to 512 columns are solved out of
+                         LDS; larger ones out of the workspace and markedly slower per unknown.
+                         The last block may be narrower.                                       */
   float damping;      /* H_d = H + damping * mean(diag H) * I (relative damping, >= 0)        */
   const uint8_t* mask_in;  /* optional c*b device mask that replaces the selection step
                               (1 = remove); NULL = select as the paper does                   */

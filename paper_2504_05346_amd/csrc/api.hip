@@ -8,7 +8,7 @@
 #include "common.h"
 
 namespace thanos {
-size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers);
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax);
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
@@ -211,6 +211,11 @@ static long long num_columns_to_remove(double p, double alpha, int64_t b) {
   return n < 0 ? 0 : n;
 }
 
+// Largest number of weights a row can lose in one block (= unknowns of its system).
+static int max_unknowns(const thanos_prune_opts* o) {
+  return (o->mode == THANOS_NM && !o->mask_in) ? o->block_size / o->m * o->n : o->block_size;
+}
+
 static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b) {
   if (!o) return THANOS_ERR_INVALID_ARG;
   if (o->mode != THANOS_UNSTRUCTURED && o->mode != THANOS_NM && o->mode != THANOS_STRUCTURED)
@@ -237,12 +242,8 @@ static thanos_status check_opts(const thanos_prune_opts* o, int64_t c, int64_t b
   if (o->outlier_fraction > 0.0 && o->mode != THANOS_NM) return THANOS_ERR_UNSUPPORTED;
   // a given mask already says which rows are pruned; the outlier rows are a selection rule
   if (o->outlier_fraction > 0.0 && o->mask_in) return THANOS_ERR_UNSUPPORTED;
-  // the per-row systems must fit the solver: at most 256 unknowns, blocks of at most 512 columns
-  if (o->mode == THANOS_NM && !o->mask_in) {
-    if (o->block_size > 512 || o->block_size / o->m * o->n > 256) return THANOS_ERR_UNSUPPORTED;
-  } else if (o->block_size > 256) {
-    return THANOS_ERR_UNSUPPORTED;
-  }
+  // the per-row systems must fit the solver: at most 2048 unknowns, blocks of at most 4096 columns
+  if (o->block_size > 4096 || max_unknowns(o) > 2048) return THANOS_ERR_UNSUPPORTED;
   (void)c;
   return THANOS_OK;
 }
@@ -289,7 +290,8 @@ thanos_status thanos_factor(const float* H, int64_t b, float damping, float* U, 
 size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opts* opts) {
   if (c <= 0 || b <= 0 || check_opts(opts, c, b) != THANOS_OK) return 0;
   if (opts->mode == THANOS_STRUCTURED) return structured_workspace_bytes(c, b);
-  size_t n = sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
+  size_t n = sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0,
+                                   max_unknowns(opts));
   if (!opts->factor_in) {
     n += align_up((size_t)b * b * sizeof(float), 256);  // U
     n += align_up((size_t)b * sizeof(float), 256);      // xnorm2
@@ -340,7 +342,8 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
   phase_mark(pt, THANOS_PHASE_FACTOR);
   char* p = reinterpret_cast<char*>(ws);
   void* sweep_ws = p;
-  p += sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0);
+  p += sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0,
+                             max_unknowns(opts));
   const float* U = opts->factor_in;
   const float* xn2 = opts->xnorm2_in;
   if (!U) {

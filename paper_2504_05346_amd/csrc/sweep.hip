@@ -472,6 +472,8 @@ struct SolveArgs {
   int bw, ldl, n, m;
   int nt_lo, nt_max;     // k_solve_tiled: rows with nt_lo <= ceil(s/32) <= nt_max; LDS holds nt_max
   int s_min;             // k_solve_wide: rows with s < s_min belong to another launch
+  float* tile_scratch;   // k_solve_tiled<.., BIG>: tile grids in global memory, one slot per workgroup
+  int64_t slot_floats;
   int defer_large;       // k_solve_mfma: rows with more unknowns than it holds belong to another launch
 };
 
@@ -1081,28 +1083,55 @@ __device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int l
   return bad;
 }
 
-template <int SEL, int NW>
-__global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(SolveArgs a) {
+// BIG = false: tiles in LDS, one workgroup per row (grid = c), systems of up to 256 unknowns in
+// blocks of up to 512 columns.  BIG = true: the same algorithm for systems of up to kBigSmax
+// unknowns in blocks of up to kBigBw columns (the large blocks of the paper's block-size
+// ablation): the tile grid of a row no longer fits LDS and lives in global memory, one slot per
+// workgroup (a.tile_scratch, a.slot_floats; the slot of a workgroup stays in the caches of its
+// compute unit's XCD), and the gridDim.x workgroups walk the rows (row = blockIdx.x,
+// blockIdx.x + gridDim.x, ...).  The row's right-hand side, multipliers, indices and the
+// block's weights stay in LDS.
+constexpr int kBigSmax = 2048;
+constexpr int kBigBw = 4096;
+static inline size_t tl_big_smem_bytes() {
+  return ((size_t)2 * kBigBw + 3 * kBigSmax + 128 + 2 * 8 * (kBigBw / 512)) * sizeof(float);
+}
+
+template <int SEL, int NW, bool BIG = false>
+__global__ __launch_bounds__(64 * NW, (BIG ? 2 : (NW == 8 ? 4 : 3))) void k_solve_tiled(SolveArgs a) {
   constexpr int NT = 64 * NW;       // threads
-  constexpr int CH = kTlBw / NT;    // block columns per thread
+  constexpr int SMAX = BIG ? kBigSmax : kTlSmax;
+  constexpr int BW = BIG ? kBigBw : kTlBw;
+  constexpr int CH = BW / NT;       // block columns per thread
   constexpr int RPT = 1024 / NT;    // tile elements per thread
+  constexpr int NC = NW * CH;       // (wavefront, column chunk) pairs
   extern __shared__ __attribute__((aligned(16))) char solve_smem[];
-  float* tiles = reinterpret_cast<float*>(solve_smem);
-  float* xtra = tiles + tl_ntiles(a.nt_max) * kTlSz;
+  float* tiles;
+  float *wrow, *key, *xtra;
+  if (BIG) {
+    tiles = a.tile_scratch + (int64_t)blockIdx.x * a.slot_floats;
+    wrow = reinterpret_cast<float*>(solve_smem);
+    key = wrow + BW;
+    xtra = key + BW;
+  } else {
+    tiles = reinterpret_cast<float*>(solve_smem);
+    xtra = tiles + tl_ntiles(a.nt_max) * kTlSz;
+    // the block's weights and metric live in the tile area until the gather overwrites them, and
+    // the lambda row is assembled there after the solve (nt_max >= 3: room for 2 * kTlBw floats)
+    wrow = tiles;
+    key = tiles + BW;
+  }
   float* u = xtra;                    // right-hand side, then y
-  float* lam = xtra + kTlSmax;
-  int* q = reinterpret_cast<int*>(xtra + 2 * kTlSmax);
-  float* aux = xtra + 3 * kTlSmax;
-  int* cnt = reinterpret_cast<int*>(aux + 128);  // per wavefront: selected, ties
-  int* eqc = cnt + 8;
-  // the block's weights and metric live in the tile area until the gather overwrites them, and
-  // the lambda row is assembled there after the solve (nt_max >= 3: room for 2 * kTlBw floats)
-  float* wrow = tiles;
-  float* key = tiles + kTlBw;
+  float* lam = xtra + SMAX;
+  int* q = reinterpret_cast<int*>(xtra + 2 * SMAX);
+  float* aux = xtra + 3 * SMAX;
+  int* cnt = reinterpret_cast<int*>(aux + 128);  // per wavefront and chunk: selected, ties
+  int* eqc = cnt + NC;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lo = lane & 31, hi = lane >> 5;
-  const int64_t i = blockIdx.x;
+  for (int64_t i = blockIdx.x; i < a.c; i += gridDim.x) {  // !BIG: gridDim.x == c, one pass
+  if (BIG) __syncthreads();  // the previous row's LDS and slot contents are dead
   const float* wrow_g = a.W + i * a.b + a.j1;
 
   // ---- selection of the block mask row M_i: column col = tid + NT * ch ----
@@ -1183,12 +1212,15 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
   __syncthreads();
   int s = 0;
 #pragma unroll
-  for (int v = 0; v < 8; ++v) s += cnt[v];
+  for (int v = 0; v < NC; ++v) s += cnt[v];
   // A block may be solved by two launches with different LDS footprints: this one takes the
   // rows with nt_lo <= ceil(s/32) <= nt_max and leaves the others untouched.
   const int nt = (s + 31) >> 5;
-  const bool fits = s <= kTlSmax;
-  if (fits ? (nt < a.nt_lo || nt > a.nt_max) : (32 * a.nt_max < kTlSmax)) return;
+  const bool fits = s <= SMAX;
+  if (fits ? (nt < a.nt_lo || nt > a.nt_max) : (32 * a.nt_max < SMAX)) {
+    if (BIG) continue;
+    return;
+  }
 #pragma unroll
   for (int ch = 0; ch < CH; ++ch) {
     const int col = tid + NT * ch;
@@ -1208,11 +1240,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
       if (col < a.bw) lam_g[col] = 0.f;
     }
     if (!fits && tid == 0) atomicCAS(a.info, 0, -(int32_t)min(i + 1, (int64_t)0x7fffffff));
+    if (BIG) continue;
     return;
   }
   __syncthreads();
-  if (tid < 32 * nt) u[tid] = (tid < s) ? wrow[q[tid]] : 0.f;
-  __syncthreads();  // wrow and key are dead from here on
+  for (int t = tid; t < 32 * nt; t += NT) u[t] = (t < s) ? wrow[q[t]] : 0.f;
+  __syncthreads();  // !BIG: wrow and key are dead from here on
 
   // ---- gather R_hat into the tiles: thread <-> (rows tid/32 + (NT/32)e, column tid%32) of a tile;
   //      up to four tiles of a tile row are fetched together, all loads unconditional from
@@ -1343,12 +1376,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
       lam[32 * p + lane] = acc;
     }
     __syncthreads();
-    if (tid < 32 * p) {  // y_j -= L_pj^T lambda_p for the tile rows above (32 p <= 224 < NT)
-      const float* Lc = tl_tile(tiles, p, tid >> 5) + (tid & 31);
-      float acc = u[tid];
+    for (int t = tid; t < 32 * p; t += NT) {  // y_j -= L_pj^T lambda_p for the tile rows above
+      const float* Lc = tl_tile(tiles, p, t >> 5) + (t & 31);
+      float acc = u[t];
 #pragma unroll
       for (int r = 0; r < 32; ++r) acc = fmaf(-Lc[r * kTlLd], lam[32 * p + r], acc);
-      u[tid] = acc;
+      u[t] = acc;
     }
     __syncthreads();
   }
@@ -1357,13 +1390,15 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 4 : 3)) void k_solve_tiled(Solv
 #pragma unroll
   for (int ch = 0; ch < CH; ++ch) wrow[tid + NT * ch] = 0.f;
   __syncthreads();
-  if (tid < s) wrow[q[tid]] = lam[tid];
+  for (int t = tid; t < s; t += NT) wrow[q[t]] = lam[t];
   __syncthreads();
 #pragma unroll
   for (int ch = 0; ch < CH; ++ch) {
     const int col = tid + NT * ch;
     if (col < a.bw) lam_g[col] = wrow[col];
   }
+  if (!BIG) return;  // one row per workgroup
+  }  // rows of this workgroup
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1577,6 +1612,7 @@ struct SweepWs {
   float* T;         // alpha > 0: W * H, c x b
   float* h;         // alpha > 0: row losses, c
   uint8_t* row_skip;  // alpha > 0: c
+  float* tile_scratch;  // large blocks: tile grids of the rows in flight
 };
 
 static char* carve(char*& p, size_t bytes) {
@@ -1591,6 +1627,14 @@ static char* carve(char*& p, size_t bytes) {
 // kSuper times longer reduction (the multipliers of all its blocks are kept, c x kSuper*B).
 constexpr int kSuper = 8;
 
+// Large blocks (more than 256 unknowns per row, or more than 512 columns): workgroups of
+// k_solve_tiled<.., BIG> that run at once, each with a slot for the tile grid of its row.
+constexpr int kBigSlots = 512;
+static inline bool needs_big(int B, int smax) { return smax > kTlSmax || B > kTlBw; }
+static inline int64_t big_slot_floats(int smax) {
+  return (int64_t)tl_ntiles((std::min(smax, kBigSmax) + 31) / 32) * kTlSz;
+}
+
 static void launch_update(hipStream_t s, UpdateArgs ua, dim3 tiles) {
   ua.gx = (int)tiles.x;
   ua.gy = (int)tiles.y;
@@ -1599,8 +1643,10 @@ static void launch_update(hipStream_t s, UpdateArgs ua, dim3 tiles) {
   hipLaunchKernelGGL(k_update, dim3(n), dim3(kXThreads), kUpdSmemBytes, s, ua);
 }
 
-size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers) {
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax) {
   size_t n = 0;
+  if (needs_big(B, smax))
+    n += align_up((size_t)std::min<int64_t>(c, kBigSlots) * big_slot_floats(smax) * 4, 256);
   n += align_up((size_t)b * 4, 256);            // sx
   n += align_up((size_t)c * B * kSuper * 4 * 2, 256);  // Lam, two super-block buffers
   n += align_up((size_t)b * b * 4, 256);        // P
@@ -1617,9 +1663,13 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers) {
   return n;
 }
 
-static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers) {
+static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers, int smax) {
   char* p = reinterpret_cast<char*>(ws);
   SweepWs w;
+  w.tile_scratch = nullptr;
+  if (needs_big(B, smax))
+    w.tile_scratch = reinterpret_cast<float*>(
+        carve(p, (size_t)std::min<int64_t>(c, kBigSlots) * big_slot_floats(smax) * 4));
   w.sx = reinterpret_cast<float*>(carve(p, (size_t)b * 4));
   w.Lam = reinterpret_cast<float*>(carve(p, (size_t)c * B * kSuper * 4 * 2));
   w.P = reinterpret_cast<float*>(carve(p, (size_t)b * b * 4));
@@ -1688,6 +1738,17 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
       a.s_min = 97;
     }
     hipLaunchKernelGGL((k_solve_wide<SEL, 128>), dim3((unsigned)a.c), dim3(128), 0, s, a);
+  } else if (smax > kTlSmax || a.bw > kTlBw) {
+    // large blocks: tile grids in global memory, persistent workgroups (two per compute unit)
+    constexpr int kNw = 8;
+    a.nt_lo = 0;
+    a.nt_max = kBigSmax / 32;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_solve_tiled<SEL, kNw, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)tl_big_smem_bytes());
+    hipLaunchKernelGGL((k_solve_tiled<SEL, kNw, true>),
+                       dim3((unsigned)std::min<int64_t>(a.c, kBigSlots)), dim3(64 * kNw),
+                       tl_big_smem_bytes(), s, a);
   } else {
     // LDS per row grows with the square of the tile rows; systems of up to 160 unknowns leave
     // room for two workgroups per compute unit, so when s varies from row to row (and may be
@@ -1726,7 +1787,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                     PhaseTimer* pt) {
   const int B = o->block_size;
   const bool outliers = n_out > 0;
-  SweepWs w = carve_ws(ws, c, b, B, outliers);
+  const int smax_all = (o->mode == THANOS_NM && !o->mask_in) ? B / o->m * o->n : B;
+  SweepWs w = carve_ws(ws, c, b, B, outliers, smax_all);
   const int64_t n = c * b;
   const unsigned nblk = (unsigned)ceil_div(n, 256);
 
@@ -1837,6 +1899,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.nt_lo = sa.nt_max = 0;
     sa.s_min = 0;
     sa.defer_large = 0;
+    sa.tile_scratch = w.tile_scratch;
+    sa.slot_floats = big_slot_floats(smax_all);
     if (o->mask_in) {
       launch_solve<SEL_GIVEN>(s, sa, bw);
     } else if (o->mode == THANOS_NM) {

@@ -51,16 +51,24 @@ def test_host_side_argument_checks(L):
                                 None, None, 0, None, None) == 1
     bad = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=126, damping=0.01)
     assert t.thanos_prune_workspace_bytes(64, 256, bad) == 0          # m does not divide B
+    # large blocks (the block-size ablation of the Experiments section): up to 4096 columns and
+    # 2048 unknowns per row; their tile grids live in the workspace, not in LDS
+    small = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=256,
+                        damping=0.01)
     big = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=512,
                       damping=0.01)
-    assert t.thanos_prune_workspace_bytes(64, 256, big) == 0          # B > 256 unsupported
-    # n:m: blocks of up to 512 columns as long as a row's system has at most 256 unknowns
+    assert t.thanos_prune_workspace_bytes(64, 256, big) > t.thanos_prune_workspace_bytes(64, 256, small)
     nm512 = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=512, damping=0.01)
     assert t.thanos_prune_workspace_bytes(64, 1024, nm512) > 0
-    nm34 = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=3, m=4, block_size=512, damping=0.01)
-    assert t.thanos_prune_workspace_bytes(64, 1024, nm34) == 0        # 384 unknowns per row
-    nm1k = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=1, m=4, block_size=1024, damping=0.01)
-    assert t.thanos_prune_workspace_bytes(64, 1024, nm1k) == 0
+    nm4k = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=2, m=4, block_size=4096, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 8192, nm4k) > 0          # 2048 unknowns per row
+    nm34 = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=3, m=4, block_size=4096, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 8192, nm34) == 0         # 3072 unknowns per row
+    nm8k = t.PruneOpts(mode=t.THANOS_NM, sparsity=0.0, n=1, m=8, block_size=8192, damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 8192, nm8k) == 0         # block wider than 4096
+    un4k = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=0.5, n=0, m=0, block_size=4096,
+                       damping=0.01)
+    assert t.thanos_prune_workspace_bytes(64, 8192, un4k) == 0         # a row may lose all 4096
     assert t.thanos_factor_workspace_bytes(1000) >= 3 * 1024 * 1024 * 4
     p1 = t.PruneOpts(mode=t.THANOS_UNSTRUCTURED, sparsity=1.0, n=0, m=0, block_size=128,
                      damping=0.01)

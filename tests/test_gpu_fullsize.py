@@ -114,8 +114,10 @@ def test_factor_properties_and_oracle(layer, host):
     assert np.linalg.norm(Ug - host.U) <= 5e-4 * np.linalg.norm(host.U)
 
 
-@pytest.mark.parametrize("block", [BLOCK, 512])   # 512: the paper's n:m setting (Experiments,
-def test_nm_sweep_full_layer(layer, host, block):  # "Models and evaluation"): 256 unknowns per row
+# 512: the paper's n:m setting (Experiments, "Models and evaluation"), 256 unknowns per row;
+# 1024: a large block of the block-size ablation, 512 unknowns per row (tile grids in global memory)
+@pytest.mark.parametrize("block", [BLOCK, 512, 1024])
+def test_nm_sweep_full_layer(layer, host, block):
     print(f"full-size 2:4 sweep, B={block}, rho={layer.rho}", flush=True)
     Wo, M, _ = _prune(layer, "nm", block)
     grp = M.view(C, B_IN // 4, 4).sum(dim=2)

@@ -119,6 +119,13 @@ def test_cfg1_nm(n, m, rho):
     (70, 1216, 512, "nm"),              # block 512 (the n:m setting of the Experiments section): 256 unknowns per row,
                                         # last block 192 wide
     (48, 768, 256, "nm14"),             # 1:4 at block 256: 64 unknowns per row in a wide block
+    # large blocks of the block-size ablation: more than 256 unknowns per row, tile grids in
+    # global memory, workgroups that walk the rows
+    (40, 2304, 1024, "nm"),             # 512 unknowns per row; last block 256 wide (LDS path)
+    (30, 1100, 512, "unstructured"),    # up to 512 unknowns, ragged last block of 76
+    (600, 1536, 1024, "nm"),            # more rows than resident workgroups
+    (24, 4608, 2048, "nm"),             # 1024 unknowns per row
+    (16, 4096, 4096, "nm14"),           # one block of 4096 columns, 1024 unknowns per row
 ])
 def test_ragged_shapes(c, b, B, mode):
     from tests.gpu_util import gpu_prune
