@@ -128,16 +128,27 @@ __global__ __launch_bounds__(kXThreads, 4) void k_block_rows(BlockRowsArgs a) {
 // Unstructured selection: exact r-th smallest metric over the residual W[:, j1:b] by a radix
 // select on the fp32 bit pattern (11 + 11 + 10 bits), all state on the device.
 //
-// The threshold of a block is predicted from the previous block's: the update that writes the
-// new weights also histograms a window of 2048 x 16 keys around the previous tau (and counts
-// what lies below it).  If the wanted rank falls inside the window, 28 bits of the key are
-// resolved, the first two radix passes leave at once and the last one resolves 4 bits.
-//
-// Launches per block: k_sel_start, k_sel_hist<0>, <1>, <2>, k_tie_rows, k_tie_scan.  There is no
-// kernel that only scans a histogram: every workgroup of the NEXT pass scans the (small)
-// histogram of the previous pass for itself, and workgroup 0 also writes the result to the
-// state for later kernels.  Fields are written by one pass and read by later ones only, so the
-// redundant scans race with nothing.
+// ONE launch per block (k_select), at most one workgroup per compute unit so that all of them
+// are resident at once.  The threshold of a block is predicted from the previous block's: the
+// update that writes the new weights also histograms a window of 2048 x 16 keys around the
+// previous tau, counts what lies below it, and every update workgroup lists the keys of its
+// tile that fall inside the window (with their rows).  Every workgroup of k_select works out for
+// itself, from the same data, whether the wanted rank falls inside the window.
+//   * It does (every block after the first on all data tried): the bin gives 28 bits of tau.
+//     The workgroups go through the per-tile lists in parallel and hand the keys of that bin to
+//     workgroup 0, which resolves the last 4 bits and the ties from them: no pass over the
+//     weights, and no device-wide fence (on this chip a release fence at device scope writes the
+//     L2 of a compute die back, ~20 us after an update has filled it; the hand-over uses atomic
+//     stores, loads and counters only, which are coherent across the dies by themselves).
+//   * It does not (first block, a threshold that moved out of the window, a full list): all
+//     workgroups run the three radix passes over the residual, separated by grid-wide barriers.
+// Every wait is bounded: a wait that does not end within kSpinMax polls ends the kernel and
+// reports kInfoSelectTimeout through info, so no wave can spin for ever.  Waiting workgroups
+// poll a word of their own (or, for the one counter workgroup 0 waits on, are alone in polling):
+// hundreds of pollers on one address make every access to that cache line take microseconds.
+// The counters of a launch (arrivals, barrier, bin list) are cleared by the update that runs
+// between two launches, never by k_select itself, so no workgroup can meet a counter that
+// another one has already reset.
 struct SelState {
   long long r_rem;      // weights still to remove (before the current block)
   long long need_eq;    // how many keys equal to tau are removed (ties, in (row, col) order)
@@ -147,13 +158,20 @@ struct SelState {
   int none;             // 1: nothing left to remove
   unsigned int win_lo;  // first 28-bit prefix (key >> 4) of the window of the NEXT block
   int pred_try;         // 1: a window was counted for this block
-  int pred_ok;          // 1: the rank fell inside the window: prefix0 holds 28 bits
-  int shift;            // low bits resolved by the last pass: 10, or 4 after a window hit
-  // rank still to resolve and resolved high bits after k_sel_start (0), after the scan of
-  // pass 0 (1), and going into the last pass (2)
-  long long rank0, rank1, rank2;
-  unsigned int prefix0, prefix1, prefix2;
+  int cand_overflow;    // an update workgroup found more window keys than it can list
+  // counters of the current k_select launch
+  unsigned int arrived; // workgroups that have handed over their part
+  unsigned int nbin;    // keys of the threshold's bin handed to workgroup 0
+  unsigned int bar;     // arrivals at the grid barriers
 };
+
+constexpr int32_t kInfoSelectTimeout = -0x7ffffff0;  // info: a bounded wait of k_select ran out
+constexpr int kSelThreads = 1024;
+constexpr int kSelMaxWgs = 256;       // at most one per compute unit: all resident at once
+constexpr unsigned int kSpinMax = 1u << 21;
+constexpr int kCandStage = 384;       // window keys one update workgroup can list (two update
+                                      // workgroups still fit the LDS of a compute unit)
+constexpr int kBinCap = 4096;         // keys of the threshold's bin that k_select can resolve
 
 __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
   return __float_as_uint(fabsf(w) * sx);
@@ -221,207 +239,130 @@ __device__ __forceinline__ long long block_sum(long long v) {
   return t;
 }
 
-// Start of a block (one workgroup): r <- r - ||M||_F^2 of the previous block (Alg. 1;
-// row_cnt[i] = weights the previous block removed from row i: one array entry per row instead of
-// thousands of atomics on one counter), then the scan of the window histogram that the previous
-// block's update filled (hist_w, plus one count per workgroup of the keys below the window).
-// The histograms of the three radix passes (3 x 2048 bins behind hist_w) are cleared here.
-__global__ __launch_bounds__(1024) void k_sel_start(SelState* __restrict__ st, int first,
-                                                    const int* __restrict__ row_cnt, int64_t c,
-                                                    unsigned int* __restrict__ hist_w,
-                                                    const unsigned int* __restrict__ below_part,
-                                                    int n_part) {
-  const int tid = threadIdx.x;
-  long long sum = 0, bsum = 0;
-  if (!first) {
-    for (int64_t i = tid; i < c; i += 1024) sum += row_cnt[i];
-    for (int e = tid; e < n_part; e += 1024) bsum += below_part[e];
-  }
-  const long long r_old = st->r_rem;
-  const bool pred_try = !first && st->pred_try != 0;
-  const unsigned int win_lo = st->win_lo;
-  const long long r_rem = r_old - block_sum<1024>(sum);
-  const long long below = block_sum<1024>(bsum);
-  const bool none = r_rem <= 0;
-  BinSel r;
-  r.bin = -1;
-  if (!none && pred_try) r = block_select_bin<1024>(hist_w, 2048, r_rem - below);
-  if (tid == 0) {
-    st->r_rem = r_rem;
-    st->none = none ? 1 : 0;
-    st->deferred = 0;
-    const bool hit = r.bin >= 0;
-    st->pred_ok = hit ? 1 : 0;
-    st->prefix0 = hit ? win_lo + (unsigned int)r.bin : 0u;
-    st->rank0 = hit ? r_rem - below - r.before : r_rem;
-  }
-  for (int e = tid; e < 4 * 2048; e += 1024) hist_w[e] = 0u;
-}
-
-// One wavefront per row; lanes stride over the residual columns (16 bytes per lane when the
-// row segment is 16-byte aligned, so that a wavefront keeps 1 KB per load instruction in flight).
 // PASS 0: bin = key >> 21.  PASS 1: keys with key>>21 == prefix, bin = (key>>10) & 2047.
-// PASS 2: keys with key>>shift == prefix, bin = the low `shift` bits (10, or 4 after a window hit);
-// also counts those keys per row.
+// PASS 2: keys with key>>10 == prefix, bin = the low 10 bits; also counts those keys (cand).
 template <int PASS>
 __device__ __forceinline__ void sel_count(unsigned int* h, unsigned int key, unsigned int prefix,
-                                          int shift, int& cand) {
+                                          int& cand) {
   if (PASS == 0) {
     atomicAdd(&h[key >> 21], 1u);
   } else if (PASS == 1) {
     if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
   } else {
-    if ((key >> shift) == prefix) {
-      atomicAdd(&h[key & ((1u << shift) - 1u)], 1u);
+    if ((key >> 10) == prefix) {
+      atomicAdd(&h[key & 1023u], 1u);
       ++cand;
     }
   }
 }
 
-// hist_in: histogram of the previous pass (scanned by every workgroup), hist_out: this pass's.
-template <int PASS>
-__global__ __launch_bounds__(256) void k_sel_hist(const float* __restrict__ W, int64_t c, int64_t b,
-                                                  int64_t j1, const float* __restrict__ sx,
-                                                  SelState* __restrict__ st,
-                                                  const unsigned int* __restrict__ hist_in,
-                                                  unsigned int* __restrict__ hist_out,
-                                                  int* __restrict__ row_cand, int vec) {
-  __shared__ unsigned int h[2048];
-  if (st->none) return;
-  const bool pred_ok = st->pred_ok != 0;
-  if (PASS < 2 && pred_ok) return;  // the window already resolved 28 bits
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  unsigned int prefix = 0u;
-  int shift = 0;
-  if (PASS == 1) {
-    const long long rank0 = st->rank0;
-    const BinSel r = block_select_bin<256>(hist_in, 2048, rank0);
-    prefix = (unsigned int)r.bin;
-    if (blockIdx.x == 0 && tid == 0) {
-      st->prefix1 = prefix;
-      st->rank1 = rank0 - r.before;
-    }
-  } else if (PASS == 2) {
-    long long rank2;
-    if (pred_ok) {
-      prefix = st->prefix0;
-      rank2 = st->rank0;
-      shift = 4;
-    } else {
-      const long long rank1 = st->rank1;
-      const BinSel r = block_select_bin<256>(hist_in, 2048, rank1);
-      prefix = (st->prefix1 << 11) | (unsigned int)r.bin;
-      rank2 = rank1 - r.before;
-      shift = 10;
-    }
-    if (blockIdx.x == 0 && tid == 0) {
-      st->prefix2 = prefix;
-      st->rank2 = rank2;
-      st->shift = shift;
-    }
+struct SelectArgs {
+  const float* W;
+  const float* sx;
+  SelState* st;
+  unsigned int* hist;              // window histogram, then the three radix passes (4 x 2048)
+  const unsigned int* below_part;  // keys below the window, one count per update workgroup
+  int n_part;                      // update workgroups (tiles) of the previous block
+  const unsigned int* cand_n;      // per tile: keys inside the window
+  const uint2* cand;               // per tile: kCandStage x (key, row)
+  unsigned long long* binlist;     // kBinCap x (row << 32 | key): the threshold's bin
+  const int* row_cnt;              // weights the previous block removed from each row
+  int* row_cand;                   // per row: keys sharing the bits resolved before the last pass
+  int* row_eq;                     // per row: keys equal to tau, then their exclusive prefix
+  float* tau_out;                  // optional: threshold of this block
+  int32_t* info;
+  int64_t c, b, j1;
+  int first;                       // first block: no window exists
+  int vec;                         // 16-byte loads of the row segments are aligned
+  unsigned int seq;                // block sequence number, >= 1
+  // One word per workgroup, each in a cache line of its own (stride kFlagStride), through which
+  // a grid barrier releases it.  Values only grow: 8 * seq + k after barrier k of block seq.
+  unsigned int* wgflag;
+};
+constexpr int kFlagStride = 32;  // words (128 bytes)
+
+// Thread 0 of the calling workgroup waits until *f has reached `want` (bounded).
+__device__ __forceinline__ unsigned int wait_word(const unsigned int* f, unsigned int want) {
+  unsigned int n = 0, v = 0;
+  for (;;) {
+    v = __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (v >= want || ++n >= kSpinMax) break;
+    __builtin_amdgcn_s_sleep(8);
   }
-  for (int e = tid; e < 2048; e += 256) h[e] = 0u;
+  return v;
+}
+
+// One radix pass of the calling workgroup over its rows (one wavefront per row; lanes stride
+// over the residual columns, 16 bytes per lane when aligned).  The workgroup's LDS histogram h
+// is added to hist_out at the end.
+template <int PASS>
+__device__ __forceinline__ void sel_pass(const SelectArgs& a, unsigned int* h, unsigned int prefix,
+                                         unsigned int* __restrict__ hist_out) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int e = tid; e < 2048; e += kSelThreads) h[e] = 0u;
   __syncthreads();
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
-  if (i < c) {
-    const float* row = W + i * b;
+  constexpr int RW = kSelThreads / 64;  // rows per workgroup and step
+  for (int64_t i = (int64_t)blockIdx.x * RW + wave; i < a.c; i += (int64_t)gridDim.x * RW) {
+    const float* row = a.W + i * a.b;
     int cand = 0;
-    if (vec) {
-      const int64_t nvec = (b - j1) >> 2;
+    if (a.vec) {
+      const int64_t nvec = (a.b - a.j1) >> 2;
       for (int64_t v = lane; v < nvec; v += 64) {
-        const int64_t j = j1 + 4 * v;
+        const int64_t j = a.j1 + 4 * v;
         const float4 w4 = *reinterpret_cast<const float4*>(row + j);
-        const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
-        sel_count<PASS>(h, metric_key(w4.x, s4.x), prefix, shift, cand);
-        sel_count<PASS>(h, metric_key(w4.y, s4.y), prefix, shift, cand);
-        sel_count<PASS>(h, metric_key(w4.z, s4.z), prefix, shift, cand);
-        sel_count<PASS>(h, metric_key(w4.w, s4.w), prefix, shift, cand);
+        const float4 s4 = *reinterpret_cast<const float4*>(a.sx + j);
+        sel_count<PASS>(h, metric_key(w4.x, s4.x), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.y, s4.y), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.z, s4.z), prefix, cand);
+        sel_count<PASS>(h, metric_key(w4.w, s4.w), prefix, cand);
       }
-      for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64)
-        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, shift, cand);
+      for (int64_t j = a.j1 + 4 * nvec + lane; j < a.b; j += 64)
+        sel_count<PASS>(h, metric_key(row[j], a.sx[j]), prefix, cand);
     } else {
-      for (int64_t j = j1 + lane; j < b; j += 64)
-        sel_count<PASS>(h, metric_key(row[j], sx[j]), prefix, shift, cand);
+      for (int64_t j = a.j1 + lane; j < a.b; j += 64)
+        sel_count<PASS>(h, metric_key(row[j], a.sx[j]), prefix, cand);
     }
     if (PASS == 2) {
       for (int off = 32; off > 0; off >>= 1) cand += __shfl_down(cand, off, 64);
-      if (lane == 0) row_cand[i] = cand;
+      if (lane == 0) a.row_cand[i] = cand;
     }
   }
   __syncthreads();
-  for (int e = tid; e < 2048; e += 256)
+  for (int e = tid; e < 2048; e += kSelThreads)
     if (h[e]) atomicAdd(&hist_out[e], h[e]);
 }
 
-// Scan of the last pass (every workgroup; workgroup 0 writes tau, the tie budget and the window
-// of the next block), then the ties: rows that hold candidates (keys sharing the bits of tau
-// resolved before the last pass) count their keys equal to tau over the residual row; other rows
-// have none.  The last pass resolves the key completely, so the chosen bin counts the keys
-// equal to tau: if all of them are removed (the usual case: one key at the threshold) their
-// order does not matter and nothing is counted.
-__global__ __launch_bounds__(256) void k_tie_rows(const float* __restrict__ W, int64_t c, int64_t b,
-                                                  int64_t j1, const float* __restrict__ sx,
-                                                  SelState* __restrict__ st,
-                                                  const unsigned int* __restrict__ hist_in,
-                                                  const int* __restrict__ row_cand,
-                                                  int* __restrict__ row_eq, int vec,
-                                                  float* __restrict__ tau_out) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
-  if (st->none) {  // uniform
-    if (i < c && lane == 0) row_eq[i] = 0;
-    if (tau_out && blockIdx.x == 0 && threadIdx.x == 0) *tau_out = -1.f;
-    return;
+// All workgroups of the launch have arrived at barrier `phase` (1, 2, ...) of this block: each
+// adds itself to a counter, and the one that completes the count releases every workgroup
+// through its own word.  Release and acquire fences at device scope on both sides: what the
+// workgroups wrote before the barrier (histogram atomics, per-row counts) is read after it.
+// Returns false if the wait ran out.
+__device__ __forceinline__ bool grid_barrier(const SelectArgs& a, unsigned int phase) {
+  __shared__ int ok, last;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    last = atomicAdd(&a.st->bar, 1u) + 1u == phase * gridDim.x ? 1 : 0;
   }
-  const int shift = st->shift;
-  const long long rank2 = st->rank2;
-  const BinSel r = block_select_bin<256>(hist_in, 1 << shift, rank2);
-  const unsigned int tau = (st->prefix2 << shift) | (unsigned int)r.bin;
-  const long long rank_eq = rank2 - r.before;  // keys equal to tau that are removed
-  const bool all = rank_eq == (long long)r.count;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    st->tau = tau;
-    if (tau_out) *tau_out = __uint_as_float(tau);
-    st->need_eq = all ? (1ll << 62) : rank_eq;
-    st->ties_all = all ? 1 : 0;
-    const unsigned int p28 = tau >> 4;
-    st->pred_try = tau != 0u ? 1 : 0;
-    st->win_lo = p28 > 1024u ? p28 - 1024u : 0u;
-  }
-  if (all || i >= c) return;  // row_eq is not read: every tie passes the test against need_eq
-  if (row_cand[i] == 0) {
-    if (lane == 0) row_eq[i] = 0;
-    return;
-  }
-  const float* row = W + i * b;
-  int n = 0;
-  if (vec) {
-    const int64_t nvec = (b - j1) >> 2;
-    for (int64_t v = lane; v < nvec; v += 64) {
-      const int64_t j = j1 + 4 * v;
-      const float4 w4 = *reinterpret_cast<const float4*>(row + j);
-      const float4 s4 = *reinterpret_cast<const float4*>(sx + j);
-      n += (metric_key(w4.x, s4.x) == tau) + (metric_key(w4.y, s4.y) == tau) +
-           (metric_key(w4.z, s4.z) == tau) + (metric_key(w4.w, s4.w) == tau);
-    }
-    for (int64_t j = j1 + 4 * nvec + lane; j < b; j += 64)
-      n += (metric_key(row[j], sx[j]) == tau) ? 1 : 0;
-  } else {
-    for (int64_t j = j1 + lane; j < b; j += 64) n += (metric_key(row[j], sx[j]) == tau) ? 1 : 0;
-  }
-  for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off, 64);
-  if (lane == 0) row_eq[i] = n;
+  __syncthreads();
+  const unsigned int want = 8u * a.seq + phase;
+  if (last)
+    for (unsigned int w = threadIdx.x; w < gridDim.x; w += kSelThreads)
+      __hip_atomic_store(a.wgflag + (size_t)w * kFlagStride, want, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0)
+    ok = wait_word(a.wgflag + (size_t)blockIdx.x * kFlagStride, want) >= want ? 1 : 0;
+  __syncthreads();
+  __threadfence();
+  return ok != 0;
 }
 
-// Exclusive prefix sum of row_eq over the rows (single workgroup, in place): afterwards
-// row_eq[i] = number of keys equal to tau in the rows before row i (ties are taken in
-// (row, column) order).  Nothing to do when every key at the threshold is removed.
-__global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int64_t c,
-                                                   const SelState* __restrict__ st) {
-  __shared__ long long wtot[16];
+// Exclusive prefix sum of row_eq over the rows by one workgroup, in place: afterwards row_eq[i]
+// = number of keys equal to tau in the rows before row i (ties are taken in (row, column) order).
+__device__ __forceinline__ void tie_prefix(int* __restrict__ row_eq, int64_t c) {
+  __shared__ long long wtot[kSelThreads / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (st->none || st->ties_all) return;
-  const int64_t per = (c + 1023) / 1024;
+  const int64_t per = (c + kSelThreads - 1) / kSelThreads;
   const int64_t lo = tid * per, hi = min(c, lo + per);
   long long s = 0;
   for (int64_t i = lo; i < hi; ++i) s += row_eq[i];
@@ -439,6 +380,213 @@ __global__ __launch_bounds__(1024) void k_tie_scan(int* __restrict__ row_eq, int
     const int v = row_eq[i];
     row_eq[i] = (int)min(run, (long long)0x7fffffff);
     run += v;
+  }
+}
+
+// Workgroup 0, at the end of the launch: the state later kernels read.  tau_valid: a threshold
+// was found (else nothing is left to remove).
+__device__ __forceinline__ void publish(const SelectArgs& a, long long r_rem, bool tau_valid,
+                                        unsigned int tau, long long rank_eq, bool all) {
+  SelState* st = a.st;
+  for (int e = threadIdx.x; e < 2048; e += kSelThreads) a.hist[e] = 0u;  // window: consumed
+  if (threadIdx.x != 0) return;
+  st->r_rem = r_rem;
+  st->none = tau_valid ? 0 : 1;
+  st->deferred = 0;
+  st->cand_overflow = 0;
+  if (!tau_valid) {
+    if (a.tau_out) *a.tau_out = -1.f;
+    return;
+  }
+  st->tau = tau;
+  if (a.tau_out) *a.tau_out = __uint_as_float(tau);
+  st->need_eq = all ? (1ll << 62) : rank_eq;
+  st->ties_all = all ? 1 : 0;
+  const unsigned int p28 = tau >> 4;
+  st->pred_try = tau != 0u ? 1 : 0;
+  st->win_lo = p28 > 1024u ? p28 - 1024u : 0u;
+}
+
+__global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
+  __shared__ unsigned int h[2048];
+  __shared__ unsigned long long bins[kBinCap];  // workgroup 0: the threshold's bin
+  __shared__ unsigned int h16[16];
+  __shared__ unsigned int s_ok;
+  SelState* st = a.st;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  constexpr int RW = kSelThreads / 64;
+
+  // ---- every workgroup: r <- r - ||M||_F^2 of the previous block (Alg. 1), the keys below the
+  //      window, and whether the window holds the wanted rank.  Nothing read here is written
+  //      before all workgroups have handed over (workgroup 0 writes the state at the very end).
+  long long sum = 0, bsum = 0;
+  if (!a.first) {
+    for (int64_t i = tid; i < a.c; i += kSelThreads) sum += a.row_cnt[i];
+    for (int e = tid; e < a.n_part; e += kSelThreads) bsum += a.below_part[e];
+  }
+  const long long r_old = st->r_rem;
+  const bool pred_try = !a.first && st->pred_try != 0 && st->cand_overflow == 0;
+  const unsigned int win_lo = st->win_lo;
+  const long long r_rem = r_old - block_sum<kSelThreads>(sum);
+  const long long below = block_sum<kSelThreads>(bsum);
+  const bool none = r_rem <= 0;
+  BinSel r;
+  r.bin = -1;
+  r.count = 0;
+  r.before = 0;
+  if (!none && pred_try) r = block_select_bin<kSelThreads>(a.hist, 2048, r_rem - below);
+  const bool hit = r.bin >= 0 && r.count <= (unsigned int)kBinCap;
+
+  if (none || hit) {
+    if (hit) {
+      // ---- the keys of the threshold's bin: one wavefront per tile list; the list of a tile
+      //      holds at most kCandStage entries, i.e. up to 6 independent loads per lane ----
+      const unsigned int prefix28 = win_lo + (unsigned int)r.bin;
+      for (int t = (int)blockIdx.x * RW + wave; t < a.n_part; t += (int)gridDim.x * RW) {
+        const unsigned int n = min(a.cand_n[t], (unsigned int)kCandStage);
+        const uint2* list = a.cand + (size_t)t * kCandStage;
+        uint2 kr[kCandStage / 64];
+#pragma unroll
+        for (int u = 0; u < kCandStage / 64; ++u) kr[u] = list[min(64 * u + lane, kCandStage - 1)];
+#pragma unroll
+        for (int u = 0; u < kCandStage / 64; ++u)
+          if ((unsigned int)(64 * u + lane) < n && (kr[u].x >> 4) == prefix28) {
+            const unsigned int slot = atomicAdd(&st->nbin, 1u);
+            if (slot < (unsigned int)kBinCap)
+              __hip_atomic_store(a.binlist + slot,
+                                 ((unsigned long long)kr[u].y << 32) | kr[u].x, __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+          }
+      }
+    }
+    // hand over: this workgroup's entries have left before it counts itself in
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) atomicAdd(&st->arrived, 1u);
+    if (blockIdx.x != 0) return;
+
+    // ---- workgroup 0: wait for the others (it is the only one polling this counter) ----
+    if (tid == 0) s_ok = wait_word(&st->arrived, gridDim.x) >= gridDim.x ? 1u : 0u;
+    __syncthreads();
+    if (!s_ok) {
+      if (tid == 0) atomicCAS(a.info, 0, kInfoSelectTimeout);
+      return;
+    }
+    if (none) {
+      publish(a, r_rem, false, 0u, 0, true);
+      return;
+    }
+    const unsigned int nbin = __hip_atomic_load(&st->nbin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (nbin != r.count) {  // the lists and the histogram disagree: cannot happen
+      if (tid == 0) atomicCAS(a.info, 0, kInfoSelectTimeout);
+      return;
+    }
+    if (tid < 16) h16[tid] = 0u;
+    __syncthreads();
+    for (unsigned int e = tid; e < nbin; e += kSelThreads) {
+      const unsigned long long v =
+          __hip_atomic_load(a.binlist + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      bins[e] = v;
+      atomicAdd(&h16[(unsigned int)v & 15u], 1u);
+    }
+    __syncthreads();
+    long long rank = r_rem - below - r.before;  // 1-based rank inside the bin
+    unsigned int low = 0, cnt_eq = 0;
+    for (unsigned int v = 0; v < 16; ++v) {     // uniform: every thread walks the 16 counts
+      if (rank <= (long long)h16[v]) {
+        low = v;
+        cnt_eq = h16[v];
+        break;
+      }
+      rank -= h16[v];
+    }
+    const unsigned int prefix28 = win_lo + (unsigned int)r.bin;
+    const unsigned int tau = (prefix28 << 4) | low;
+    const bool all = rank == (long long)cnt_eq;
+    if (!all) {
+      // ties to rank (some, not all, keys equal to tau are removed), in (row, column) order:
+      // row_eq[i] = keys equal to tau in the rows before row i, counted from the bin in LDS
+      for (int64_t i = tid; i < a.c; i += kSelThreads) {
+        int before = 0;
+        for (unsigned int e = 0; e < nbin; ++e)
+          before += ((unsigned int)bins[e] == tau && (unsigned int)(bins[e] >> 32) < (unsigned int)i) ? 1 : 0;
+        a.row_eq[i] = before;
+      }
+    }
+    publish(a, r_rem, true, tau, rank, all);
+    return;
+  }
+
+  // ---- radix passes over the residual, all workgroups (the histograms of the passes were
+  //      cleared by the update, or by the fill at the start of the sweep) ----
+  unsigned int* hist_a = a.hist + 2048;
+  unsigned int* hist_b = a.hist + 2 * 2048;
+  unsigned int* hist_c = a.hist + 3 * 2048;
+  bool ok = true;
+  sel_pass<0>(a, h, 0u, hist_a);
+  ok = grid_barrier(a, 1u);
+  const BinSel r0 = block_select_bin<kSelThreads>(hist_a, 2048, r_rem);
+  const unsigned int prefix1 = (unsigned int)r0.bin;
+  const long long rank1 = r_rem - r0.before;
+  if (ok) {
+    sel_pass<1>(a, h, prefix1, hist_b);
+    ok = grid_barrier(a, 2u);
+  }
+  const BinSel r1 = block_select_bin<kSelThreads>(hist_b, 2048, rank1);
+  const unsigned int prefix2 = (prefix1 << 11) | (unsigned int)r1.bin;
+  const long long rank2 = rank1 - r1.before;
+  if (ok) {
+    sel_pass<2>(a, h, prefix2, hist_c);
+    ok = grid_barrier(a, 3u);
+  }
+  if (!ok) {
+    if (tid == 0) atomicCAS(a.info, 0, kInfoSelectTimeout);
+    return;
+  }
+  // The last pass resolves the key completely, so the chosen bin counts the keys equal to tau:
+  // if all of them are removed (the usual case: one key at the threshold) their order does not
+  // matter and nothing is ranked.
+  const BinSel r2 = block_select_bin<kSelThreads>(hist_c, 1024, rank2);
+  const unsigned int tau = (prefix2 << 10) | (unsigned int)r2.bin;
+  const long long rank_eq = rank2 - r2.before;  // keys equal to tau that are removed
+  const bool all = rank_eq == (long long)r2.count;
+  if (all) {
+    if (blockIdx.x == 0) publish(a, r_rem, true, tau, rank_eq, true);
+    return;
+  }
+  // rows that hold candidates (keys sharing the 22 bits resolved before the last pass) count
+  // their keys equal to tau over the residual row; other rows have none
+  for (int64_t i = (int64_t)blockIdx.x * RW + wave; i < a.c; i += (int64_t)gridDim.x * RW) {
+    int n = 0;
+    if (a.row_cand[i] != 0) {
+      const float* row = a.W + i * a.b;
+      if (a.vec) {
+        const int64_t nvec = (a.b - a.j1) >> 2;
+        for (int64_t v = lane; v < nvec; v += 64) {
+          const int64_t j = a.j1 + 4 * v;
+          const float4 w4 = *reinterpret_cast<const float4*>(row + j);
+          const float4 s4 = *reinterpret_cast<const float4*>(a.sx + j);
+          n += (metric_key(w4.x, s4.x) == tau) + (metric_key(w4.y, s4.y) == tau) +
+               (metric_key(w4.z, s4.z) == tau) + (metric_key(w4.w, s4.w) == tau);
+        }
+        for (int64_t j = a.j1 + 4 * nvec + lane; j < a.b; j += 64)
+          n += (metric_key(row[j], a.sx[j]) == tau) ? 1 : 0;
+      } else {
+        for (int64_t j = a.j1 + lane; j < a.b; j += 64)
+          n += (metric_key(row[j], a.sx[j]) == tau) ? 1 : 0;
+      }
+      for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off, 64);
+    }
+    if (lane == 0) a.row_eq[i] = n;
+  }
+  if (!grid_barrier(a, 4u)) {
+    if (tid == 0) atomicCAS(a.info, 0, kInfoSelectTimeout);
+    return;
+  }
+  if (blockIdx.x == 0) {
+    tie_prefix(a.row_eq, a.c);
+    publish(a, r_rem, true, tau, rank_eq, false);
   }
 }
 
@@ -464,7 +612,7 @@ struct SolveArgs {
   float* Lam;            // c x ldl
   const SelState* st;    // SEL_THRESHOLD
   SelState* st_rw;
-  const int* row_eq;     // exclusive tie prefix per row (k_tie_rows + k_tie_scan; see ties_before)
+  const int* row_eq;     // exclusive tie prefix per row (k_select; see ties_before)
   int* row_cnt;          // SEL_THRESHOLD: number of weights removed from row i in this block
   const uint8_t* row_skip;  // optional, c bytes: 1 = row is left untouched (outlier row)
   int32_t* info;
@@ -1421,17 +1569,21 @@ struct UpdateArgs {
   // k_tie_rows / k_sel_start); hist == nullptr switches this off.
   unsigned int* hist;         // 2048 bins, global
   unsigned int* below_part;   // keys below the window, one count per workgroup
-  const SelState* st;
+  unsigned int* cand_n;       // per workgroup: keys inside the window ...
+  uint2* cand;                // ... and the keys with their rows, kCandStage slots per workgroup
+  SelState* st;
   const float* sx;
   int gx, gy;                 // tile grid (set by launch_update)
 };
 
-constexpr size_t kUpdSmemBytes = kXSmemBytes + 2048 * sizeof(unsigned int) + 16 * sizeof(unsigned int);
+constexpr size_t kUpdSmemBytes = kXSmemBytes + 2048 * sizeof(unsigned int) +
+                                 16 * sizeof(unsigned int) + kCandStage * sizeof(uint2);
 
 __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
   unsigned int* hw = reinterpret_cast<unsigned int*>(sm + kXSmemBytes);  // window histogram
-  unsigned int* nb_wave = hw + 2048;
+  unsigned int* nb_wave = hw + 2048;  // 8 counts per wavefront, then: staged keys, list offset
+  uint2* stage = reinterpret_cast<uint2*>(nb_wave + 16);
   // Tile of this workgroup.  Consecutive workgroup ids go to the eight XCDs in turn, each with
   // an L2 of its own: XCD x takes the row tiles x*rp .. x*rp + rp - 1 and walks them column by
   // column, so that it reads one eighth of the multipliers and every tile of P_k once.
@@ -1455,8 +1607,10 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   const float* Bm = a.P + a.prow0 * a.b + n0;   // (k,n) at B[k*b + n]
   // does this tile feed the next selection?  (uniform per workgroup)
   const bool win = a.hist != nullptr && !a.st->none && a.st->pred_try && n0 + n_ext > a.zj2;
-  if (win)
+  if (win) {
     for (int e = threadIdx.x; e < 2048; e += kXThreads) hw[e] = 0u;  // barriers follow in the product
+    if (threadIdx.x == 0) nb_wave[8] = 0u;                            // staged keys
+  }
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
@@ -1471,10 +1625,16 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   // window count of one new weight (columns right of the block only)
   const unsigned int wlo = win ? a.st->win_lo : 0u;
   unsigned int nb = 0;
-  auto count = [&](float w, float sxj) {
-    const unsigned int p28 = metric_key(w, sxj) >> 4;
-    if (p28 < wlo) ++nb;
-    else if (p28 - wlo < 2048u) atomicAdd(&hw[p28 - wlo], 1u);
+  auto count = [&](float w, float sxj, int row) {
+    const unsigned int key = metric_key(w, sxj);
+    const unsigned int p28 = key >> 4;
+    if (p28 < wlo) {
+      ++nb;
+    } else if (p28 - wlo < 2048u) {
+      atomicAdd(&hw[p28 - wlo], 1u);
+      const unsigned int k = atomicAdd(&nb_wave[8], 1u);
+      if (k < (unsigned int)kCandStage) stage[k] = make_uint2(key, (unsigned int)(m0 + row));
+    }
   };
   if (m_ext == kTM && n_ext == kTN && a.vec_w) {  // whole tile, aligned pairs
     const bool z0 = in_block && cg >= a.zj1 && cg < a.zj2;
@@ -1497,8 +1657,8 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
       o.x = (z0 && (mk[i] & 0xffu)) ? 0.f : old[i].x - t.x;
       o.y = (z1 && (mk[i] >> 8)) ? 0.f : old[i].y - t.y;
       *reinterpret_cast<float2*>(Wg + (int64_t)row * a.b) = o;
-      if (h0) count(o.x, sx0);
-      if (h1) count(o.y, sx1);
+      if (h0) count(o.x, sx0, row);
+      if (h1) count(o.y, sx1, row);
     }
   } else {
     for (int i = 0; i < 16; ++i) {
@@ -1511,7 +1671,7 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
           const bool z = in_block && cg + e >= a.zj1 && cg + e < a.zj2 && Mg[off] != 0;
           const float o = z ? 0.f : Wg[off] - T[row * kXCLd + c0 + e];
           Wg[off] = o;
-          if (win && cg + e >= a.zj2) count(o, a.sx[cg + e]);
+          if (win && cg + e >= a.zj2) count(o, a.sx[cg + e], row);
         }
       }
     }
@@ -1522,14 +1682,29 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
   if (lane == 0) nb_wave[wave] = nb;
   __syncthreads();
+  const int tile = by * a.gx + bx;
   if (threadIdx.x == 0) {
     unsigned int t = 0;
     for (int v = 0; v < kXThreads / 64; ++v) t += nb_wave[v];
-    a.below_part[by * a.gx + bx] = t;
+    a.below_part[tile] = t;
+    unsigned int n = win ? nb_wave[8] : 0u;
+    if (n > (unsigned int)kCandStage) {  // more window keys than a list holds: no prediction
+      a.st->cand_overflow = 1;
+      n = 0u;
+    }
+    a.cand_n[tile] = n;
   }
-  if (win)
-    for (int e = threadIdx.x; e < 2048; e += kXThreads)
-      if (hw[e]) atomicAdd(&a.hist[e], hw[e]);
+  if (blockIdx.x == 0) {
+    // between two launches of k_select: the histograms of its radix passes and its counters
+    for (int e = threadIdx.x; e < 3 * 2048; e += kXThreads) a.hist[2048 + e] = 0u;
+    if (threadIdx.x == 0) a.st->arrived = a.st->nbin = a.st->bar = 0u;
+  }
+  if (!win) return;
+  const unsigned int n = min(nb_wave[8], (unsigned int)kCandStage);
+  uint2* list = a.cand + (size_t)tile * kCandStage;
+  for (unsigned int e = threadIdx.x; e < n; e += kXThreads) list[e] = stage[e];
+  for (int e = threadIdx.x; e < 2048; e += kXThreads)
+    if (hw[e]) atomicAdd(&a.hist[e], hw[e]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1608,6 +1783,10 @@ struct SweepWs {
   int* row_cand;
   int* row_eq;
   unsigned int* below_part;  // one count per workgroup of the block update
+  unsigned int* cand_n;      // per update workgroup: keys inside the selection window ...
+  uint2* cand;               // ... and (key, row) of each, kCandStage slots per workgroup
+  unsigned long long* binlist;  // k_select: the keys of the threshold's bin
+  unsigned int* wgflag;      // k_select: one word per workgroup, a cache line each
   float* Hf;        // alpha > 0: symmetric copy of H, b x b
   float* T;         // alpha > 0: W * H, c x b
   float* h;         // alpha > 0: row losses, c
@@ -1654,6 +1833,10 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int sma
   n += align_up(sizeof(SelState), 256);         // state
   n += 2 * align_up((size_t)c * 4, 256);        // row_cand, row_eq
   n += align_up((size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4, 256);  // below_part
+  n += align_up((size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4, 256);  // cand_n
+  n += align_up((size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * kCandStage * sizeof(uint2), 256);  // cand
+  n += align_up((size_t)kBinCap * 8, 256);                              // binlist
+  n += align_up((size_t)kSelMaxWgs * kFlagStride * 4, 256);                     // wgflag
   if (outliers) {
     n += align_up((size_t)b * b * 4, 256);      // Hf
     n += align_up((size_t)c * b * 4, 256);      // T
@@ -1679,6 +1862,12 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers, in
   w.row_eq = reinterpret_cast<int*>(carve(p, (size_t)c * 4));
   w.below_part = reinterpret_cast<unsigned int*>(
       carve(p, (size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4));
+  w.cand_n = reinterpret_cast<unsigned int*>(
+      carve(p, (size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * 4));
+  w.cand = reinterpret_cast<uint2*>(
+      carve(p, (size_t)ceil_div(b, kTN) * ceil_div(c, kTM) * kCandStage * sizeof(uint2)));
+  w.binlist = reinterpret_cast<unsigned long long*>(carve(p, (size_t)kBinCap * 8));
+  w.wgflag = reinterpret_cast<unsigned int*>(carve(p, (size_t)kSelMaxWgs * kFlagStride * 4));
   w.Hf = w.T = w.h = nullptr;
   w.row_skip = nullptr;
   if (outliers) {
@@ -1690,6 +1879,15 @@ static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers, in
   return w;
 }
 
+// Compute units of the current device (k_select launches at most one workgroup per unit).
+static int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+    return 32;
+  return n;
+}
+
 __global__ void k_init_state(SelState* st, long long r) {
   st->r_rem = r;
   st->need_eq = 0;
@@ -1699,10 +1897,8 @@ __global__ void k_init_state(SelState* st, long long r) {
   st->none = (r <= 0) ? 1 : 0;
   st->win_lo = 0u;
   st->pred_try = 0;
-  st->pred_ok = 0;
-  st->shift = 10;
-  st->rank0 = st->rank1 = st->rank2 = 0;
-  st->prefix0 = st->prefix1 = st->prefix2 = 0u;
+  st->cand_overflow = 0;
+  st->arrived = st->nbin = st->bar = 0u;
 }
 
 template <int SEL>
@@ -1827,6 +2023,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
   const bool unstructured = (o->mode == THANOS_UNSTRUCTURED) && o->mask_in == nullptr;
   if (unstructured) {
     hipLaunchKernelGGL(k_fill_u32, dim3(32), dim3(256), 0, s, w.hist, (int64_t)4 * 2048, 0u);
+    hipLaunchKernelGGL(k_fill_u32, dim3(kSelMaxWgs * kFlagStride / 256), dim3(256), 0, s, w.wgflag,
+                       (int64_t)kSelMaxWgs * kFlagStride, 0u);
     hipLaunchKernelGGL(k_init_state, dim3(1), dim3(1), 0, s, w.st, r_total);
     THANOS_LAUNCH_CHECK();
   }
@@ -1856,23 +2054,33 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       // 16-byte loads need W + i*b + j1 and sx + j1 aligned (W, sx come 256-byte aligned)
       const int sel_vec = (b % 4 == 0 && j1 % 4 == 0 &&
                            reinterpret_cast<uintptr_t>(W) % 16 == 0) ? 1 : 0;
-      // the previous block's update counted the window around its threshold while it wrote
-      // the new weights
-      unsigned int* hist_a = w.hist + 2048;
-      unsigned int* hist_b = w.hist + 2 * 2048;
-      unsigned int* hist_c = w.hist + 3 * 2048;
-      hipLaunchKernelGGL(k_sel_start, dim3(1), dim3(1024), 0, s, w.st, j1 == 0 ? 1 : 0, w.row_cand, c,
-                         w.hist, w.below_part, win_parts);
-      hipLaunchKernelGGL(k_sel_hist<0>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         nullptr, hist_a, w.row_cand, sel_vec);
-      hipLaunchKernelGGL(k_sel_hist<1>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         hist_a, hist_b, w.row_cand, sel_vec);
-      hipLaunchKernelGGL(k_sel_hist<2>, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         hist_b, hist_c, w.row_cand, sel_vec);
-      hipLaunchKernelGGL(k_tie_rows, dim3(rows4), dim3(256), 0, s, W, c, b, j1, w.sx, w.st,
-                         hist_c, w.row_cand, w.row_eq, sel_vec,
-                         o->threshold_out ? o->threshold_out + blk : nullptr);
-      hipLaunchKernelGGL(k_tie_scan, dim3(1), dim3(1024), 0, s, w.row_eq, c, w.st);
+      // the previous block's update counted the window around its threshold, and listed the
+      // keys inside it, while it wrote the new weights
+      SelectArgs ga;
+      ga.W = W;
+      ga.sx = w.sx;
+      ga.st = w.st;
+      ga.hist = w.hist;
+      ga.below_part = w.below_part;
+      ga.n_part = win_parts;
+      ga.cand_n = w.cand_n;
+      ga.cand = w.cand;
+      ga.binlist = w.binlist;
+      ga.row_cnt = w.row_cand;
+      ga.row_cand = w.row_cand;
+      ga.row_eq = w.row_eq;
+      ga.tau_out = o->threshold_out ? o->threshold_out + blk : nullptr;
+      ga.info = info;
+      ga.c = c;
+      ga.b = b;
+      ga.j1 = j1;
+      ga.first = j1 == 0 ? 1 : 0;
+      ga.vec = sel_vec;
+      ga.seq = (unsigned int)(blk + 1);
+      ga.wgflag = w.wgflag;
+      const unsigned sel_wgs = (unsigned)std::min<int64_t>(std::min(kSelMaxWgs, compute_units()),
+                                                           ceil_div(c, kSelThreads / 64));
+      hipLaunchKernelGGL(k_select, dim3(sel_wgs), dim3(kSelThreads), 0, s, ga);
       THANOS_LAUNCH_CHECK();
     }
     phase_mark(pt, THANOS_PHASE_SOLVE);
@@ -1887,7 +2095,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.st_rw = w.st;
     sa.row_skip = w.row_skip;
     sa.row_eq = w.row_eq;
-    sa.row_cnt = w.row_cand;  // free once k_tie_rows has read the candidate flags
+    sa.row_cnt = w.row_cand;  // free once k_select has read the candidate flags
     sa.info = info;
     sa.c = c;
     sa.b = b;
@@ -1917,7 +2125,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       if (feed) win_parts = (int)(grid.x * grid.y);
       UpdateArgs ua{W, lam_sb + loff, w.P, mask, c, b, j1, j1, sb_end, j1, j1 + bw, bw, ldl,
                     (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w,
-                    feed ? w.hist : nullptr, w.below_part, w.st, w.sx};
+                    feed ? w.hist : nullptr, w.below_part, w.cand_n, w.cand, w.st, w.sx};
       launch_update(s, ua, grid);
       THANOS_LAUNCH_CHECK();
     }
@@ -1927,8 +2135,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       if (next_end < b) {  // rest: right of the next super-block, second stream
         THANOS_CHECK(aux.fork((int)(2 * sbi)));
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
-                      nullptr};
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr, nullptr,
+                      nullptr, nullptr};
         dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
         launch_update(aux.stream, ua, grid);
         THANOS_LAUNCH_CHECK();
@@ -1936,8 +2144,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
       if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
       {  // strip: the columns of the next super-block
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr,
-                      nullptr};
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr, nullptr,
+                      nullptr, nullptr};
         dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
         launch_update(s, ua, grid);
         THANOS_LAUNCH_CHECK();
