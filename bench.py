@@ -18,6 +18,8 @@ Prints ONE JSON line:
   * `rooflines`: one entry per phase (algorithmic flops and bytes / phase time);
   * `extra`: the second workload of the target, the same layer at 50 % unstructured sparsity,
     timed the same way in the same run (only when the default workload is run);
+  * `measured_peaks`: what this GPU sustains in a loop of nothing but fp16 MFMAs (smooth and
+    random operands, with the shader clock it runs at) and in a plain HBM copy;
   * `cpu_baseline`: the float64 oracle timed on a bounded sample on the host cores.
 """
 from __future__ import annotations
@@ -80,6 +82,9 @@ def parse_args():
     ap.add_argument("--no-extra", action="store_true",
                     help="do not time the 50 %% unstructured workload next to the default one")
     ap.add_argument("--phases-only", action="store_true", help="skip the oracle, print phases")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the measured ceilings of this GPU (MFMA-only loop with its shader "
+                         "clock on smooth and on random operands, HBM copy; ~0.1 s)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain 1 GiB device copy first (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -320,6 +325,16 @@ def main():
                          "config": {"workload": x["workload"], "accumulate_calls": args.chunks},
                          "phases_ms": x["phases_ms"], "kept_fraction": x["kept_fraction"],
                          "rooflines": x.get("rooflines")}]
+    if not args.no_measured_peaks:
+        # what this chip sustains, next to the data-sheet peaks the fractions are quoted against:
+        # its matrix cores are clocked down under load, and more so when the operands toggle
+        from paper_2504_05346_amd import peak_probe
+        mp = peak_probe.measure(torch)
+        out["measured_peaks"] = mp
+        ceil = [m["tflops"] for m in mp["mfma_f16"]
+                if m["operands"] == "random" and m["run"] == "sustained"]
+        if ceil:
+            out["roofline"]["frac_of_measured_mfma_only_rate"] = out["roofline"]["achieved"] / ceil[0]
     if not (args.no_cpu_baseline or args.phases_only):
         out["cpu_baseline"] = cpu_baseline(args, W, X, torch)
     print(json.dumps(out))

@@ -45,8 +45,23 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
+PROBE_SRC = os.path.join(CSRC, "probe", "peak_probe.hip")
+PROBE_LIB = os.path.join(HERE, "libthanos_probe.so")
+
+
+def build_probe(force: bool = False) -> str:
+    """libthanos_probe.so: stand-alone microbenchmarks (measured matrix-core and HBM ceilings)."""
+    if force or _stale(PROBE_LIB, [PROBE_SRC]):
+        cmd = [HIPCC, *FLAGS, "-shared", PROBE_SRC, "-o", PROBE_LIB]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed for the probe:\n{r.stdout}\n{r.stderr}")
+    return PROBE_LIB
+
+
 def build(force: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
+    build_probe(force)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIB, objs):

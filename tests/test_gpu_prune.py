@@ -322,6 +322,32 @@ def test_exact_ties_follow_row_major_order(B):
     np.testing.assert_array_equal(Mg, orc.nm_mask(W, np.diag(H32), 2, 4))
 
 
+@pytest.mark.parametrize("need", [1, 5, 14])
+def test_few_ties_at_the_threshold_in_later_blocks(need):
+    """Distinct metrics except 15 equal ones exactly at the threshold, scattered over all blocks,
+    of which `need` are removed: every block after the first resolves its threshold from the
+    window the previous update counted and must rank the ties in (row, column) order over its
+    residual.  Diagonal Hessian: no weight moves, so the mask is one global psi."""
+    from tests.gpu_util import gpu_prune
+    g = np.random.default_rng(3)
+    c, b, N = 64, 512, 64 * 512
+    vals = (np.arange(1, N + 1, dtype=np.float32) / np.float32(N))       # exact in fp32, distinct
+    r = N // 2
+    lo = r - need                                    # ranks lo+1 .. lo+15 become ties
+    vals[lo:lo + 15] = vals[lo]
+    W = (g.permutation(vals) * g.choice(np.array([-1.0, 1.0], dtype=np.float32), size=N)
+         ).reshape(c, b).astype(np.float32)
+    H32 = np.eye(b, dtype=np.float32)
+    tie_cols = np.nonzero(np.abs(W) == vals[lo])[1]
+    assert len(tie_cols) == 15 and len(set(tie_cols // 128)) >= 3      # ties in several blocks
+    Wg, Mg, info = gpu_prune(W, H32, mode="unstructured", p=0.5, B=128, damp=0.01)
+    assert info == 0
+    Mref = orc.psi(W, np.ones(b), r)
+    assert int(Mref[np.abs(W) == vals[lo]].sum()) == need               # the cut is inside the ties
+    np.testing.assert_array_equal(Mg, Mref)
+    np.testing.assert_array_equal(Wg, W * (1 - Mref))
+
+
 @pytest.mark.parametrize("mode", ["unstructured", "nm"])
 def test_seventeen_row_tiles(mode):
     # 2176 rows = 17 row tiles of the trailing update: its tile order by XCD (bands of
