@@ -119,6 +119,10 @@ def test_cfg1_nm(n, m, rho):
     (70, 1216, 512, "nm"),              # block 512 (the n:m setting of the Experiments section): 256 unknowns per row,
                                         # last block 192 wide
     (48, 768, 256, "nm14"),             # 1:4 at block 256: 64 unknowns per row in a wide block
+    # b not a multiple of 8 at more than toy size: the scalar / 8-byte paths of the sweep
+    (300, 1100, 128, "unstructured"),   # b % 8 == 4
+    (300, 1100, 128, "nm"),
+    (257, 1030, 128, "unstructured"),   # b % 4 == 2: nothing 16-byte aligned from row to row
     # large blocks of the block-size ablation: more than 256 unknowns per row, tile grids in
     # global memory, workgroups that walk the rows
     (40, 2304, 1024, "nm"),             # 512 unknowns per row; last block 256 wide (LDS path)
