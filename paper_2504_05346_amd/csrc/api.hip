@@ -8,12 +8,13 @@
 #include "common.h"
 
 namespace thanos {
-size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax);
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax, bool comp);
+bool sweep_uses_complement(const thanos_prune_opts* o, int64_t b);
 thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
                     void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
-                    PhaseTimer* pt);
+                    PhaseTimer* pt, const float* Lfac, int64_t ldL);
 size_t structured_workspace_bytes(int64_t c, int64_t b);
 thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                          const float* H, float damping, long long s_cols, long long n_out,
@@ -291,7 +292,7 @@ size_t thanos_prune_workspace_bytes(int64_t c, int64_t b, const thanos_prune_opt
   if (c <= 0 || b <= 0 || check_opts(opts, c, b) != THANOS_OK) return 0;
   if (opts->mode == THANOS_STRUCTURED) return structured_workspace_bytes(c, b);
   size_t n = sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0,
-                                   max_unknowns(opts));
+                                   max_unknowns(opts), sweep_uses_complement(opts, b));
   if (!opts->factor_in) {
     n += align_up((size_t)b * b * sizeof(float), 256);  // U
     n += align_up((size_t)b * sizeof(float), 256);      // xnorm2
@@ -343,9 +344,11 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
   char* p = reinterpret_cast<char*>(ws);
   void* sweep_ws = p;
   p += sweep_workspace_bytes(c, b, opts->block_size, opts->outlier_fraction > 0.0,
-                             max_unknowns(opts));
+                             max_unknowns(opts), sweep_uses_complement(opts, b));
   const float* U = opts->factor_in;
   const float* xn2 = opts->xnorm2_in;
+  const float* Lfac = nullptr;  // lower factor of the index-reversed damped Hessian (this call's)
+  int64_t ldL = 0;
   if (!U) {
     float* Uw = reinterpret_cast<float*>(p);
     p += align_up((size_t)b * b * sizeof(float), 256);
@@ -355,6 +358,7 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
     if (st != THANOS_OK) return st;
     U = Uw;
     xn2 = xw;
+    Lfac = factor_L(p, b, &ldL);
   } else {
     hipLaunchKernelGGL(k_zero_info, dim3(1), dim3(1), 0, s, info_dev);
     THANOS_LAUNCH_CHECK();
@@ -364,7 +368,7 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
   const long long n_out = num_outlier_rows(opts->outlier_fraction, c);
   phase_mark(pt, THANOS_PHASE_PREP);
   thanos_status st = sweep(s, W_in, wdt, c, b, H, U, xn2, opts, r_total, n_out, W_out, W_out_cast,
-                           mask_out, sweep_ws, info_dev, single_stream, pt);
+                           mask_out, sweep_ws, info_dev, single_stream, pt, Lfac, ldL);
   if (pt) {
     const thanos_status tc = pt->collect(opts->phase_ms_out);
     if (st == THANOS_OK) st = tc;

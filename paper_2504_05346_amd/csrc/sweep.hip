@@ -125,6 +125,49 @@ __global__ __launch_bounds__(kXThreads, 4) void k_block_rows(BlockRowsArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Inverses of the blocks' G matrices, for rows that lose more than half of a block.
+// With G = P_k[:, :bw] = U_bb^T U_bb (U_bb the diagonal block of the factor), K = G^{-1} =
+// V_bb V_bb^T, where V = U^{-1} is the reverse Cholesky factor the factorisation leaves behind
+// (V[x][y] = L[b-1-x][b-1-y], L = its workspace's lower factor of the index-reversed matrix), and
+// the diagonal block of the inverse of a triangular matrix is the inverse of its diagonal block:
+// no inversion is computed.  Kc[blk][a][j] = sum_{m >= max(a, j)} V[j1+a][j1+m] V[j1+j][j1+m],
+// row stride B.  One workgroup per 32 x 32 tile of a block.
+__global__ __launch_bounds__(256) void k_comp_blocks(const float* __restrict__ L, int64_t ldL,
+                                                     int64_t b, int B, float* __restrict__ Kc) {
+  __shared__ float Va[32][33], Vj[32][33];
+  const int64_t j1 = (int64_t)blockIdx.z * B;
+  const int bw = (int)min((int64_t)B, b - j1);
+  const int a0 = 32 * blockIdx.y, c0 = 32 * blockIdx.x;
+  if (a0 >= bw || c0 >= bw) return;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // ty 0..7
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  auto V = [&](int x, int y) -> float {  // block-local indices, zero outside the upper triangle
+    if (x >= bw || y >= bw || y < x) return 0.f;
+    return L[(b - 1 - (j1 + x)) * ldL + (b - 1 - (j1 + y))];
+  };
+  for (int m0 = (max(a0, c0) / 32) * 32; m0 < bw; m0 += 32) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      Va[ty + 8 * e][tx] = V(a0 + ty + 8 * e, m0 + tx);
+      Vj[ty + 8 * e][tx] = V(c0 + ty + 8 * e, m0 + tx);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float t = acc[e];
+#pragma unroll
+      for (int m = 0; m < 32; ++m) t = fmaf(Va[ty + 8 * e][m], Vj[tx][m], t);
+      acc[e] = t;
+    }
+    __syncthreads();
+  }
+  float* out = Kc + (int64_t)blockIdx.z * B * B;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (a0 + ty + 8 * e < bw && c0 + tx < bw) out[(int64_t)(a0 + ty + 8 * e) * B + c0 + tx] = acc[e];
+}
+
+// ------------------------------------------------------------------------------------------
 // Unstructured selection: exact r-th smallest metric over the residual W[:, j1:b] by a radix
 // select on the fp32 bit pattern (11 + 11 + 10 bits), all state on the device.
 //
@@ -622,6 +665,8 @@ struct SolveArgs {
   int s_min;             // k_solve_wide: rows with s < s_min belong to another launch
   float* tile_scratch;   // k_solve_tiled<.., BIG>: tile grids in global memory, one slot per workgroup
   int64_t slot_floats;
+  const float* Kc;       // k_solve_tiled: inverse of this block's G (bw x bw, row stride ldk), or
+  int ldk;               // nullptr; rows that lose more than half of the block are solved through it
   int defer_large;       // k_solve_mfma: rows with more unknowns than it holds belong to another launch
 };
 
@@ -1231,6 +1276,65 @@ __device__ __forceinline__ bool tl_pivots(f32x16 D, float* Dt, float* aux, int l
   return bad;
 }
 
+// y[j] = sum_a x[a] * K[a * ldk + j], j < bw (bw a multiple of 4, K 16-byte aligned rows), for a
+// workgroup of NW wavefronts; x and y in LDS.  Rows with x[a] == 0 are skipped (uniform test).
+// !BIG (bw <= 512): the wavefronts split the rows a, each lane holds up to two groups of four
+// columns, partial sums meet in part[NW][bw] (LDS) and are added in a fixed order.
+// BIG: every wavefront owns column groups and walks all rows; no partial sums.
+// Barriers inside; x must be complete on entry, y is complete on return.
+template <int NW, bool BIG>
+__device__ __forceinline__ void tl_matvec(const float* x, int bw, const float* __restrict__ K,
+                                          int ldk, float* y, float* part) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ng = bw >> 2;
+  if (BIG) {
+    for (int g = 64 * wave + lane; g < ng; g += 64 * NW) {
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+      for (int a = 0; a < bw; ++a) {
+        const float xa = x[a];
+        const float4 k4 = *reinterpret_cast<const float4*>(K + (int64_t)a * ldk + 4 * g);
+        acc.x = fmaf(xa, k4.x, acc.x);
+        acc.y = fmaf(xa, k4.y, acc.y);
+        acc.z = fmaf(xa, k4.z, acc.z);
+        acc.w = fmaf(xa, k4.w, acc.w);
+      }
+      *reinterpret_cast<float4*>(y + 4 * g) = acc;
+    }
+    __syncthreads();
+    return;
+  }
+  const int per = (bw + NW - 1) / NW;
+  const int alo = wave * per, ahi = min(bw, alo + per);
+  float4 acc[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
+  const int g0 = min(lane, ng - 1), g1 = min(lane + 64, ng - 1);  // clamped: loads stay in bounds
+#pragma unroll 4
+  for (int a = alo; a < ahi; ++a) {
+    const float xa = x[a];
+    if (xa == 0.f) continue;
+    const float4 k0 = *reinterpret_cast<const float4*>(K + (int64_t)a * ldk + 4 * g0);
+    const float4 k1 = *reinterpret_cast<const float4*>(K + (int64_t)a * ldk + 4 * g1);
+    acc[0].x = fmaf(xa, k0.x, acc[0].x);
+    acc[0].y = fmaf(xa, k0.y, acc[0].y);
+    acc[0].z = fmaf(xa, k0.z, acc[0].z);
+    acc[0].w = fmaf(xa, k0.w, acc[0].w);
+    acc[1].x = fmaf(xa, k1.x, acc[1].x);
+    acc[1].y = fmaf(xa, k1.y, acc[1].y);
+    acc[1].z = fmaf(xa, k1.z, acc[1].z);
+    acc[1].w = fmaf(xa, k1.w, acc[1].w);
+  }
+  if (lane < ng) *reinterpret_cast<float4*>(part + wave * bw + 4 * lane) = acc[0];
+  if (lane + 64 < ng) *reinterpret_cast<float4*>(part + wave * bw + 4 * (lane + 64)) = acc[1];
+  __syncthreads();
+  for (int j = tid; j < bw; j += 64 * NW) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += part[w * bw + j];
+    y[j] = t;
+  }
+  __syncthreads();
+}
+
 // BIG = false: tiles in LDS, one workgroup per row (grid = c), systems of up to 256 unknowns in
 // blocks of up to 512 columns.  BIG = true: the same algorithm for systems of up to kBigSmax
 // unknowns in blocks of up to kBigBw columns (the large blocks of the paper's block-size
@@ -1361,24 +1465,48 @@ __global__ __launch_bounds__(64 * NW, (BIG ? 2 : (NW == 8 ? 4 : 3))) void k_solv
   int s = 0;
 #pragma unroll
   for (int v = 0; v < NC; ++v) s += cnt[v];
+  // A row that loses more than half of the block is solved through the complement: with
+  // K = G^{-1}, kept set k of the block and w~ = (u on q, 0 on k),
+  //     (G_qq)^{-1} = K_qq - K_qk (K_kk)^{-1} K_kq,   so   lambda = ((w~ - y~) K)_q
+  // with y~ = (0 on q, y on k), y K_kk = (w~ K)_k: a system of bw - s unknowns instead of s,
+  // and never more than half a block.  (Same accuracy: K is formed from the factor directly.)
+  const bool comp = a.Kc != nullptr && 2 * s > a.bw;  // uniform per workgroup
+  const int ns = comp ? a.bw - s : s;                  // unknowns of this row's system
+  if (SEL == SEL_THRESHOLD) {
+    if (tid == 0) a.row_cnt[i] = s;  // summed at the start of the next block
+  }
+#pragma unroll
+  for (int ch = 0; ch < CH; ++ch) {
+    const int col = tid + NT * ch;
+    if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[ch] ? 1 : 0;
+  }
   // A block may be solved by two launches with different LDS footprints: this one takes the
-  // rows with nt_lo <= ceil(s/32) <= nt_max and leaves the others untouched.
-  const int nt = (s + 31) >> 5;
-  const bool fits = s <= SMAX;
+  // rows with nt_lo <= ceil(ns/32) <= nt_max and leaves the others untouched.
+  const int nt = (ns + 31) >> 5;
+  const bool fits = ns <= SMAX;
   if (fits ? (nt < a.nt_lo || nt > a.nt_max) : (32 * a.nt_max < SMAX)) {
     if (BIG) continue;
     return;
+  }
+  // the solved set: removed columns, or kept columns of the block when solving the complement
+  bool ins[CH];
+#pragma unroll
+  for (int ch = 0; ch < CH; ++ch) ins[ch] = comp ? (tid + NT * ch < a.bw && !sel[ch]) : sel[ch];
+  if (comp) {
+    __syncthreads();  // all counts of the removed set have been read
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+      bal[ch] = __ballot(ins[ch]);
+      if (lane == 0) cnt[NW * ch + wave] = __popcll(bal[ch]);
+    }
+    __syncthreads();
   }
 #pragma unroll
   for (int ch = 0; ch < CH; ++ch) {
     const int col = tid + NT * ch;
     int before = 0;
     for (int v = 0; v < NW * ch + wave; ++v) before += cnt[v];
-    if (sel[ch] && fits) q[before + __popcll(bal[ch] & ((1ull << lane) - 1ull))] = col;
-    if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[ch] ? 1 : 0;
-  }
-  if (SEL == SEL_THRESHOLD) {
-    if (tid == 0) a.row_cnt[i] = s;  // summed at the start of the next block
+    if (ins[ch] && fits) q[before + __popcll(bal[ch] & ((1ull << lane) - 1ull))] = col;
   }
   float* lam_g = a.Lam + i * a.ldl;
   if (s == 0 || !fits) {  // !fits cannot happen for a launch chosen by the host
@@ -1392,26 +1520,41 @@ __global__ __launch_bounds__(64 * NW, (BIG ? 2 : (NW == 8 ? 4 : 3))) void k_solv
     return;
   }
   __syncthreads();
-  for (int t = tid; t < 32 * nt; t += NT) u[t] = (t < s) ? wrow[q[t]] : 0.f;
+  // partial sums of the complement's matrix-vector products: behind wrow and key in the tile
+  // area (nt_max >= 3: 6 tiles = 6336 floats >= 2 * 512 + 8 * 512)
+  float* part = BIG ? nullptr : tiles + 2 * BW;
+  if (!comp) {
+    for (int t = tid; t < 32 * nt; t += NT) u[t] = (t < s) ? wrow[q[t]] : 0.f;
+  } else {
+    // right-hand side (w~ K)_k: x = w~ in `key`, the product lands in `wrow` (the row's weights
+    // stay in registers)
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) key[tid + NT * ch] = sel[ch] ? wv[ch] : 0.f;
+    __syncthreads();
+    tl_matvec<NW, BIG>(key, a.bw, a.Kc, a.ldk, wrow, part);
+    for (int t = tid; t < 32 * nt; t += NT) u[t] = (t < ns) ? wrow[q[t]] : 0.f;
+  }
   __syncthreads();  // !BIG: wrow and key are dead from here on
 
   // ---- gather R_hat into the tiles: thread <-> (rows tid/32 + (NT/32)e, column tid%32) of a tile;
   //      up to four tiles of a tile row are fetched together, all loads unconditional from
   //      clamped (valid) indices and masked when stored ----
-  {
-    const float* G = a.P + a.j1 * a.b + a.j1;
+  if (ns > 0) {
+    // R_hat = G[q, q], or K[k, k] for the complement
+    const float* G = comp ? a.Kc : a.P + a.j1 * a.b + a.j1;
+    const int64_t ldg = comp ? (int64_t)a.ldk : a.b;
     const int tr = tid >> 5, tc = tid & 31;
     for (int ti = 0; ti < nt; ++ti) {
       const float* grow[RPT];
 #pragma unroll
       for (int e = 0; e < RPT; ++e)
-        grow[e] = G + (int64_t)q[min(32 * ti + tr + (NT / 32) * e, s - 1)] * a.b;
+        grow[e] = G + (int64_t)q[min(32 * ti + tr + (NT / 32) * e, ns - 1)] * ldg;
       for (int tj0 = 0; tj0 <= ti; tj0 += 4) {
         float v[4][RPT];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int tj = min(tj0 + t, ti);
-          const int qc = q[min(32 * tj + tc, s - 1)];
+          const int qc = q[min(32 * tj + tc, ns - 1)];
 #pragma unroll
           for (int e = 0; e < RPT; ++e) v[t][e] = grow[e][qc];
         }
@@ -1425,7 +1568,7 @@ __global__ __launch_bounds__(64 * NW, (BIG ? 2 : (NW == 8 ? 4 : 3))) void k_solv
             for (int e = 0; e < RPT; ++e) {
               const int rr = 32 * ti + tr + (NT / 32) * e;
               const float ident = (rr == cc) ? 1.f : 0.f;
-              T[(tr + (NT / 32) * e) * kTlLd + tc] = (rr < s && cc < s) ? v[t][e] : ident;
+              T[(tr + (NT / 32) * e) * kTlLd + tc] = (rr < ns && cc < ns) ? v[t][e] : ident;
             }
           }
         }
@@ -1438,7 +1581,7 @@ __global__ __launch_bounds__(64 * NW, (BIG ? 2 : (NW == 8 ? 4 : 3))) void k_solv
   //      that eliminates a diagonal tile rotates, so that concurrent workgroups of a compute
   //      unit do not run this latency-bound step on the same SIMD. ----
   bool bad = false;
-  if (wave == ((int)blockIdx.x & (NW - 1))) {
+  if (nt > 0 && wave == ((int)blockIdx.x & (NW - 1))) {
     f32x16 D;
 #pragma unroll
     for (int r = 0; r < 16; ++r) D[r] = tiles[tl_row(r, hi) * kTlLd + lo];
@@ -1535,15 +1678,31 @@ __global__ __launch_bounds__(64 * NW, (BIG ? 2 : (NW == 8 ? 4 : 3))) void k_solv
   }
 
   // ---- lambda row: zeros except lambda_k at column q_k ----
+  if (!comp) {
 #pragma unroll
-  for (int ch = 0; ch < CH; ++ch) wrow[tid + NT * ch] = 0.f;
-  __syncthreads();
-  for (int t = tid; t < s; t += NT) wrow[q[t]] = lam[t];
-  __syncthreads();
+    for (int ch = 0; ch < CH; ++ch) wrow[tid + NT * ch] = 0.f;
+    __syncthreads();
+    for (int t = tid; t < s; t += NT) wrow[q[t]] = lam[t];
+    __syncthreads();
 #pragma unroll
-  for (int ch = 0; ch < CH; ++ch) {
-    const int col = tid + NT * ch;
-    if (col < a.bw) lam_g[col] = wrow[col];
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
+      if (col < a.bw) lam_g[col] = wrow[col];
+    }
+  } else {
+    // lambda = ((w~ - y~) K)_q: x = w on the removed columns, -y on the kept ones
+    __syncthreads();
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) key[tid + NT * ch] = sel[ch] ? wv[ch] : 0.f;
+    __syncthreads();
+    for (int t = tid; t < ns; t += NT) key[q[t]] = -lam[t];
+    __syncthreads();
+    tl_matvec<NW, BIG>(key, a.bw, a.Kc, a.ldk, wrow, part);
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+      const int col = tid + NT * ch;
+      if (col < a.bw) lam_g[col] = sel[ch] ? wrow[col] : 0.f;
+    }
   }
   if (!BIG) return;  // one row per workgroup
   }  // rows of this workgroup
@@ -1792,6 +1951,7 @@ struct SweepWs {
   float* h;         // alpha > 0: row losses, c
   uint8_t* row_skip;  // alpha > 0: c
   float* tile_scratch;  // large blocks: tile grids of the rows in flight
+  float* Kc;            // inverse of every block's G (B x B per block), or nullptr
 };
 
 static char* carve(char*& p, size_t bytes) {
@@ -1822,8 +1982,21 @@ static void launch_update(hipStream_t s, UpdateArgs ua, dim3 tiles) {
   hipLaunchKernelGGL(k_update, dim3(n), dim3(kXThreads), kUpdSmemBytes, s, ua);
 }
 
-size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax) {
+// Whether rows that lose more than half of a block are solved through K = G^{-1} (see
+// k_comp_blocks, k_solve_tiled): only the tiled solver does it (blocks wider than 128 columns),
+// the blocks' K come from the factor of the same call (not available with a given factor), the
+// matrix-vector products read K in aligned groups of four columns, and n:m patterns that remove
+// at most half of every group never need it.
+bool sweep_uses_complement(const thanos_prune_opts* o, int64_t b) {
+  const int B = o->block_size;
+  if (o->factor_in || B <= 128 || B % 4 != 0 || b % 4 != 0) return false;
+  if (o->mode == THANOS_NM && !o->mask_in && 2 * o->n <= o->m) return false;
+  return true;
+}
+
+size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax, bool comp) {
   size_t n = 0;
+  if (comp) n += align_up((size_t)ceil_div(b, B) * B * B * 4, 256);  // K blocks
   if (needs_big(B, smax))
     n += align_up((size_t)std::min<int64_t>(c, kBigSlots) * big_slot_floats(smax) * 4, 256);
   n += align_up((size_t)b * 4, 256);            // sx
@@ -1846,9 +2019,12 @@ size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int sma
   return n;
 }
 
-static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers, int smax) {
+static SweepWs carve_ws(void* ws, int64_t c, int64_t b, int B, bool outliers, int smax,
+                        bool comp) {
   char* p = reinterpret_cast<char*>(ws);
   SweepWs w;
+  w.Kc = nullptr;
+  if (comp) w.Kc = reinterpret_cast<float*>(carve(p, (size_t)ceil_div(b, B) * B * B * 4));
   w.tile_scratch = nullptr;
   if (needs_big(B, smax))
     w.tile_scratch = reinterpret_cast<float*>(
@@ -1903,6 +2079,8 @@ __global__ void k_init_state(SelState* st, long long r) {
 
 template <int SEL>
 static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
+  if (a.bw <= 128) a.Kc = nullptr;  // only the tiled solver knows the complement form
+  if (a.Kc) smax = SEL == SEL_NM ? std::min(smax, a.bw - smax) : a.bw / 2;  // unknowns per row
   if (a.bw <= 128 && smax <= 64) {
     constexpr int kWpb = 4;
     const size_t smem = kWpb * sizeof(SolveMfmaSmem<2>);
@@ -1980,11 +2158,12 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
                     void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
-                    PhaseTimer* pt) {
+                    PhaseTimer* pt, const float* Lfac, int64_t ldL) {
   const int B = o->block_size;
   const bool outliers = n_out > 0;
   const int smax_all = (o->mode == THANOS_NM && !o->mask_in) ? B / o->m * o->n : B;
-  SweepWs w = carve_ws(ws, c, b, B, outliers, smax_all);
+  const bool comp = sweep_uses_complement(o, b) && Lfac != nullptr;
+  SweepWs w = carve_ws(ws, c, b, B, outliers, smax_all, sweep_uses_complement(o, b));
   const int64_t n = c * b;
   const unsigned nblk = (unsigned)ceil_div(n, 256);
 
@@ -2018,6 +2197,12 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                                          (int)kUpdSmemBytes));
     hipLaunchKernelGGL(k_block_rows, grid, dim3(kXThreads), kXSmemBytes, s, a);
     THANOS_LAUNCH_CHECK();
+    if (comp) {
+      const unsigned nt32 = (unsigned)ceil_div(B, 32);
+      hipLaunchKernelGGL(k_comp_blocks, dim3(nt32, nt32, (unsigned)ceil_div(b, B)), dim3(256), 0, s,
+                         Lfac, ldL, b, B, w.Kc);
+      THANOS_LAUNCH_CHECK();
+    }
   }
 
   const bool unstructured = (o->mode == THANOS_UNSTRUCTURED) && o->mask_in == nullptr;
@@ -2109,6 +2294,8 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.defer_large = 0;
     sa.tile_scratch = w.tile_scratch;
     sa.slot_floats = big_slot_floats(smax_all);
+    sa.Kc = (comp && bw > 128) ? w.Kc + blk * (int64_t)B * B : nullptr;
+    sa.ldk = B;
     if (o->mask_in) {
       launch_solve<SEL_GIVEN>(s, sa, bw);
     } else if (o->mode == THANOS_NM) {

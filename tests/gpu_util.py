@@ -42,8 +42,8 @@ def gpu_factor(H32: np.ndarray, damping: float):
 
 
 def gpu_prune(W: np.ndarray, H32: np.ndarray, *, mode: str, p=0.0, n=0, m=0, B=128, damp=0.01,
-              mask_in=None, cast=False, U=None, xnorm2=None, alpha=0.0):
-    """Run thanos_prune_layer; returns (W_hat fp32, mask uint8, info[, W_cast])."""
+              mask_in=None, cast=False, U=None, xnorm2=None, alpha=0.0, tau=False):
+    """Run thanos_prune_layer; returns (W_hat fp32, mask uint8, info[, W_cast][, tau per block])."""
     c, b = W.shape
     Wd = dev(W)
     Hd = dev(H32.astype(np.float32)) if H32 is not None else None
@@ -60,6 +60,10 @@ def gpu_prune(W: np.ndarray, H32: np.ndarray, *, mode: str, p=0.0, n=0, m=0, B=1
         Ud, xd = dev(U.astype(np.float32)), dev(xnorm2.astype(np.float32))
         keep += [Ud, xd]
         o.factor_in, o.xnorm2_in = Ud.data_ptr(), xd.data_ptr()
+    tau_d = None
+    if tau:
+        tau_d = torch.full(((b + B - 1) // B,), -2.0, dtype=torch.float32, device="cuda")
+        o.threshold_out = tau_d.data_ptr()
     nbytes = th.thanos_prune_workspace_bytes(c, b, o)
     assert nbytes > 0, "options rejected"
     ws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
@@ -72,4 +76,6 @@ def gpu_prune(W: np.ndarray, H32: np.ndarray, *, mode: str, p=0.0, n=0, m=0, B=1
     out = (Wo.cpu().numpy(), M.cpu().numpy(), int(info.item()))
     if cast:
         out = out + (Wc.cpu().numpy(),)
+    if tau:
+        out = out + (tau_d.cpu().numpy(),)
     return out
