@@ -173,13 +173,14 @@ __global__ __launch_bounds__(256) void k_comp_blocks(const float* __restrict__ L
 //
 // ONE launch per block (k_select), at most one workgroup per compute unit so that all of them
 // are resident at once.  The threshold of a block is predicted from the previous block's: the
-// update that writes the new weights also histograms a window of 2048 x 16 keys around the
-// previous tau, counts what lies below it, and every update workgroup lists the keys of its
+// update that writes the new weights also histograms a window of 2048 bins (of 16 to 64 keys)
+// around the previous tau, counts what lies below it, and every update workgroup lists the keys of its
 // tile that fall inside the window (with their rows).  Every workgroup of k_select works out for
 // itself, from the same data, whether the wanted rank falls inside the window.
-//   * It does (every block after the first on all data tried): the bin gives 28 bits of tau.
+//   * It does (every block after the first on all data tried): the bin gives all but the last
+//     4 to 6 bits of tau.
 //     The workgroups go through the per-tile lists in parallel and hand the keys of that bin to
-//     workgroup 0, which resolves the last 4 bits and the ties from them: no pass over the
+//     workgroup 0, which resolves the last bits and the ties from them: no pass over the
 //     weights, and no device-wide fence (on this chip a release fence at device scope writes the
 //     L2 of a compute die back, ~20 us after an update has filled it; the hand-over uses atomic
 //     stores, loads and counters only, which are coherent across the dies by themselves).
@@ -199,7 +200,8 @@ struct SelState {
   int deferred;         // 1: some row of the block was left to the second solver launch
   unsigned int tau;     // r-th smallest key
   int none;             // 1: nothing left to remove
-  unsigned int win_lo;  // first 28-bit prefix (key >> 4) of the window of the NEXT block
+  unsigned int win_lo;  // first bin (key >> win_shift) of the window of the NEXT block
+  int win_shift;        // keys per bin of that window = 2^win_shift (kWinShiftMin .. kWinShiftMax)
   int pred_try;         // 1: a window was counted for this block
   int cand_overflow;    // an update workgroup found more window keys than it can list
   // counters of the current k_select launch
@@ -215,6 +217,12 @@ constexpr unsigned int kSpinMax = 1u << 21;
 constexpr int kCandStage = 384;       // window keys one update workgroup can list (two update
                                       // workgroups still fit the LDS of a compute unit)
 constexpr int kBinCap = 4096;         // keys of the threshold's bin that k_select can resolve
+// The window has 2048 bins of 2^shift keys, 1024 on either side of the last threshold.  The bin
+// width follows the drift of the threshold from block to block (at least 8 times the last step
+// must fit into half the window): 16 keys per bin (+- 0.2 % of tau) while the threshold moves
+// little, up to 64 (+- 0.8 %) when it moves more; the lists of window keys grow in proportion,
+// which is what bounds the width.
+constexpr int kWinShiftMin = 4, kWinShiftMax = 6;
 
 __device__ __forceinline__ unsigned int metric_key(float w, float sx) {
   return __float_as_uint(fabsf(w) * sx);
@@ -441,19 +449,27 @@ __device__ __forceinline__ void publish(const SelectArgs& a, long long r_rem, bo
     if (a.tau_out) *a.tau_out = -1.f;
     return;
   }
+  // bin width of the next window from the step the threshold has just taken
+  int shift = kWinShiftMin;
+  if (!a.first && st->tau != 0u) {
+    const unsigned int prev = st->tau;
+    const unsigned int step = tau > prev ? tau - prev : prev - tau;
+    while (shift < kWinShiftMax && (1024u << shift) < 8u * (unsigned long long)step) ++shift;
+  }
   st->tau = tau;
   if (a.tau_out) *a.tau_out = __uint_as_float(tau);
   st->need_eq = all ? (1ll << 62) : rank_eq;
   st->ties_all = all ? 1 : 0;
-  const unsigned int p28 = tau >> 4;
+  const unsigned int pb = tau >> shift;
   st->pred_try = tau != 0u ? 1 : 0;
-  st->win_lo = p28 > 1024u ? p28 - 1024u : 0u;
+  st->win_shift = shift;
+  st->win_lo = pb > 1024u ? pb - 1024u : 0u;
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   __shared__ unsigned int h[2048];
   __shared__ unsigned long long bins[kBinCap];  // workgroup 0: the threshold's bin
-  __shared__ unsigned int h16[16];
+  __shared__ unsigned int h16[1 << kWinShiftMax];  // counts of the bin's keys by their low bits
   __shared__ unsigned int s_ok;
   SelState* st = a.st;
   const int tid = threadIdx.x;
@@ -471,6 +487,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   const long long r_old = st->r_rem;
   const bool pred_try = !a.first && st->pred_try != 0 && st->cand_overflow == 0;
   const unsigned int win_lo = st->win_lo;
+  const int wsh = st->win_shift;
   const long long r_rem = r_old - block_sum<kSelThreads>(sum);
   const long long below = block_sum<kSelThreads>(bsum);
   const bool none = r_rem <= 0;
@@ -494,7 +511,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
         for (int u = 0; u < kCandStage / 64; ++u) kr[u] = list[min(64 * u + lane, kCandStage - 1)];
 #pragma unroll
         for (int u = 0; u < kCandStage / 64; ++u)
-          if ((unsigned int)(64 * u + lane) < n && (kr[u].x >> 4) == prefix28) {
+          if ((unsigned int)(64 * u + lane) < n && (kr[u].x >> wsh) == prefix28) {
             const unsigned int slot = atomicAdd(&st->nbin, 1u);
             if (slot < (unsigned int)kBinCap)
               __hip_atomic_store(a.binlist + slot,
@@ -525,18 +542,19 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
       if (tid == 0) atomicCAS(a.info, 0, kInfoSelectTimeout);
       return;
     }
-    if (tid < 16) h16[tid] = 0u;
+    const unsigned int nlow = 1u << wsh;
+    if (tid < (int)nlow) h16[tid] = 0u;
     __syncthreads();
     for (unsigned int e = tid; e < nbin; e += kSelThreads) {
       const unsigned long long v =
           __hip_atomic_load(a.binlist + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       bins[e] = v;
-      atomicAdd(&h16[(unsigned int)v & 15u], 1u);
+      atomicAdd(&h16[(unsigned int)v & (nlow - 1u)], 1u);
     }
     __syncthreads();
     long long rank = r_rem - below - r.before;  // 1-based rank inside the bin
     unsigned int low = 0, cnt_eq = 0;
-    for (unsigned int v = 0; v < 16; ++v) {     // uniform: every thread walks the 16 counts
+    for (unsigned int v = 0; v < nlow; ++v) {   // uniform: every thread walks the counts
       if (rank <= (long long)h16[v]) {
         low = v;
         cnt_eq = h16[v];
@@ -545,7 +563,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
       rank -= h16[v];
     }
     const unsigned int prefix28 = win_lo + (unsigned int)r.bin;
-    const unsigned int tau = (prefix28 << 4) | low;
+    const unsigned int tau = (prefix28 << wsh) | low;
     const bool all = rank == (long long)cnt_eq;
     if (!all) {
       // ties to rank (some, not all, keys equal to tau are removed), in (row, column) order:
@@ -1783,10 +1801,11 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   const uint8_t* Mg = a.mask + m0 * a.b + cg;
   // window count of one new weight (columns right of the block only)
   const unsigned int wlo = win ? a.st->win_lo : 0u;
+  const int wsh = win ? a.st->win_shift : kWinShiftMin;
   unsigned int nb = 0;
   auto count = [&](float w, float sxj, int row) {
     const unsigned int key = metric_key(w, sxj);
-    const unsigned int p28 = key >> 4;
+    const unsigned int p28 = key >> wsh;
     if (p28 < wlo) {
       ++nb;
     } else if (p28 - wlo < 2048u) {
@@ -2072,6 +2091,7 @@ __global__ void k_init_state(SelState* st, long long r) {
   st->tau = 0u;
   st->none = (r <= 0) ? 1 : 0;
   st->win_lo = 0u;
+  st->win_shift = kWinShiftMin;
   st->pred_try = 0;
   st->cand_overflow = 0;
   st->arrived = st->nbin = st->bar = 0u;

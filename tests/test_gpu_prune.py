@@ -421,6 +421,30 @@ def test_threshold_jumps_between_blocks():
     np.testing.assert_array_equal(Mg, Mo64)
 
 
+@pytest.mark.parametrize("growth", [1.002, 1.006, 1.02])
+def test_threshold_drifts_steadily(growth):
+    # Column blocks whose scale grows by a constant factor: the global threshold moves by a
+    # steady step from block to block -- a fraction of the narrowest selection window, about its
+    # half-width, and beyond the widest one -- so the sweep meets windows of every bin width and
+    # blocks that fall back to the radix passes.
+    from tests.gpu_util import gpu_prune
+    from tests.fullsize_util import check_unstructured_rows
+    c, b, B = 96, 2048, 128
+    W, H32 = _layer(c, b, 4096, "f32", rho=0.0, seed=21)
+    W = (W * (growth ** (np.arange(b) // B)).astype(np.float32)[None, :]).astype(np.float32)
+    print(f"threshold drift, growth {growth} per block", flush=True)
+    Wg, Mg, info, tau = gpu_prune(W, H32, mode="unstructured", p=0.5, B=B, tau=True)
+    assert info == 0 and int(Mg.sum()) == c * b // 2
+    H = H32.astype(np.float64)
+    Wo, Mo = orc.prune_unstructured(W, H, 0.5, B, 0.01)
+    step = np.abs(np.diff(tau)) / tau[:-1]
+    print(f"  relative step of the threshold per block: median {np.median(step):.1e}, "
+          f"max {step.max():.1e}; masks differ at {int((Mg != Mo).sum())} positions", flush=True)
+    assert (Mg != Mo).mean() < 1e-4
+    check_unstructured_rows(W, H, orc.inverse_factor(orc.damped(H, 0.01)), Wg.astype(np.float64), Mg,
+                            tau, 0.5, B, 0.01, f"drift {growth}")
+
+
 def test_sparsity_edge_values():
     from tests.gpu_util import gpu_prune
     W, H32 = _layer(16, 128, 512, "f32", seed=7)
