@@ -170,3 +170,40 @@ def test_diagnostic_phase_timing_gives_the_same_result(mode):
                                              ctypes.byref(o), Wo2.data_ptr(), None, M2.data_ptr(),
                                              info2.data_ptr(), None)
     assert st == 2
+
+
+@pytest.mark.parametrize("mode", ["unstructured", "nm"])
+def test_two_calls_on_two_streams_at_once(mode):
+    """Two sweeps enqueued back to back on two streams (own buffers and workspaces each) run side
+    by side on the device -- helper streams from the pool, and for the unstructured mode two
+    selection kernels whose workgroups wait for each other inside the launch -- and give what
+    each gives alone."""
+    import torch
+    import paper_2504_05346_amd as th
+    layers = []
+    for k, (c, b) in enumerate([(512, 1536), (384, 2048)]):
+        W, X = _layer(c, b, 2048, seed=30 + k, dtype="f16")
+        Wd = torch.from_numpy(W).cuda()
+        H = torch.from_numpy(orc.hessian(X).astype(np.float32)).cuda()
+        layers.append((Wd, H))
+    o = th.PruneOpts(mode=th.THANOS_NM if mode == "nm" else th.THANOS_UNSTRUCTURED, sparsity=0.5,
+                     n=2, m=4, block_size=128, damping=0.01)
+    alone = []
+    for Wd, H in layers:
+        Wo, _, M, info, _ = _prune_torch(Wd, H, o, cast=False)
+        torch.cuda.synchronize()
+        assert int(info.item()) == 0
+        alone.append((Wo.clone(), M.clone()))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(3):
+        outs.clear()
+        for (Wd, H), s in zip(layers, streams):
+            with torch.cuda.stream(s):
+                outs.append(_prune_torch(Wd, H, o, stream=s, cast=False))
+        for s in streams:
+            s.synchronize()
+        for (Wo, _, M, info, _), (Wa, Ma) in zip(outs, alone):
+            assert int(info.item()) == 0
+            assert torch.equal(M, Ma) and torch.equal(Wo, Wa)
