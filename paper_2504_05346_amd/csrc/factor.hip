@@ -502,7 +502,8 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
   if (!tri.ok) return THANOS_ERR_HIP;
   int tri_done = -1;  // blocks 0..tri_done have been handed to the inversion
   int tri_batches = 0;
-  constexpr int tri_cap = 512;  // workgroups of one launch while the factorisation runs
+  constexpr int tri_cap = 512;  // workgroups of one launch while the factorisation runs (256 or
+                                // 384 measured the same, 192 and fewer slower)
   auto trinv_upto = [&](int kdone) -> thanos_status {
     // blocks <= kdone: diagonal inverse known, panel below solved (recorded on s by the caller)
     THANOS_CHECK(tri.fork(tri_batches));
@@ -577,17 +578,10 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
       const int next_end = std::min(nb, ob_end + kOuter);
       const int64_t kk = (int64_t)(ob_end - ob_begin) * NB;
       const float* lp = Ap + ((int64_t)ob_end * NB) * bp + (int64_t)ob_begin * NB;
-      // fork: the rest (rows and columns >= next_end) on the second stream
-      if (next_end < nb) {
-        THANOS_CHECK(aux.fork(2 * ob));
-        const int64_t rest = bp - (int64_t)next_end * NB;
-        const float* lr = lp + ((int64_t)(next_end - ob_end) * NB) * bp;
-        float* cr = Ap + ((int64_t)next_end * NB) * bp + (int64_t)next_end * NB;
-        st = gemm_f32(aux.stream, false, false, rest, rest, kk, -1.f, lr, bp, lr, bp, 1.f, cr, bp,
-                      true);
-        if (st != THANOS_OK) return st;
-      }
-      // the strip of the next outer block: it was last written by the previous rest
+      // The strip of the next outer block first: it is on the critical path (the next diagonal
+      // block waits for it) and gets the chip to itself for the ~25 us it needs; launched behind
+      // the rest, it shared the compute units with that much larger product and took 80-100 us.
+      // It was last written by the previous rest.
       if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
       {
         const int64_t rows = bp - (int64_t)ob_end * NB;
@@ -596,7 +590,17 @@ thanos_status factor(hipStream_t s, const float* H, int64_t b, float damping, fl
         st = gemm_f32(s, false, false, rows, cols, kk, -1.f, lp, bp, lp, bp, 1.f, cs, bp, true);
         if (st != THANOS_OK) return st;
       }
+      // fork: the rest (rows and columns >= next_end) on the second stream, next to the
+      // latency-bound chain of the next outer block (the fork point lies behind the strip, which
+      // costs the rest nothing: the two write disjoint columns)
       if (next_end < nb) {
+        THANOS_CHECK(aux.fork(2 * ob));
+        const int64_t rest = bp - (int64_t)next_end * NB;
+        const float* lr = lp + ((int64_t)(next_end - ob_end) * NB) * bp;
+        float* cr = Ap + ((int64_t)next_end * NB) * bp + (int64_t)next_end * NB;
+        st = gemm_f32(aux.stream, false, false, rest, rest, kk, -1.f, lr, bp, lr, bp, 1.f, cr, bp,
+                      true);
+        if (st != THANOS_OK) return st;
         THANOS_CHECK(aux.record(2 * ob + 1));
         pending_join = 2 * ob + 1;
       }

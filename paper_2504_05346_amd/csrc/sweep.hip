@@ -2339,6 +2339,18 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     if (super > 1 && j1 + bw == sb_end && sb_end < b) {  // all blocks of the super-block
       const int64_t next_end = std::min<int64_t>(b, sb_end + (int64_t)super * B);
       const int kk = (int)(sb_end - sb_start);
+      // The strip (the columns of the next super-block) first: the next block's solve waits for
+      // it, so it gets the chip before the much larger rest does.  It was last written by the
+      // previous rest.
+      if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
+      {
+        UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
+                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr, nullptr,
+                      nullptr, nullptr};
+        dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
+        launch_update(s, ua, grid);
+        THANOS_LAUNCH_CHECK();
+      }
       if (next_end < b) {  // rest: right of the next super-block, second stream
         THANOS_CHECK(aux.fork((int)(2 * sbi)));
         UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, next_end, b, 0, 0, kk, ldl,
@@ -2347,17 +2359,6 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
         dim3 grid((unsigned)ceil_div(b - next_end, kTN), (unsigned)ceil_div(c, kTM));
         launch_update(aux.stream, ua, grid);
         THANOS_LAUNCH_CHECK();
-      }
-      if (pending_join >= 0) THANOS_CHECK(aux.join(pending_join));
-      {  // strip: the columns of the next super-block
-        UpdateArgs ua{W, lam_sb, w.P, mask, c, b, sb_start, sb_end, next_end, 0, 0, kk, ldl,
-                      (B % 4 == 0) ? 1 : 0, aligned_b ? 1 : 0, pair_w, nullptr, nullptr, nullptr, nullptr,
-                      nullptr, nullptr};
-        dim3 grid((unsigned)ceil_div(next_end - sb_end, kTN), (unsigned)ceil_div(c, kTM));
-        launch_update(s, ua, grid);
-        THANOS_LAUNCH_CHECK();
-      }
-      if (next_end < b) {
         THANOS_CHECK(aux.record((int)(2 * sbi + 1)));
         pending_join = (int)(2 * sbi + 1);
       }
