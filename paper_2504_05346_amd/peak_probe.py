@@ -1,10 +1,14 @@
 """Measured ceilings of the GPU (matrix-core fp16 rate of an MFMA-only loop with the shader
 clock it runs at, HBM copy bandwidth), from libthanos_probe.so.
 
-    python -m paper_2504_05346_amd.peak_probe          # prints one JSON object
+    python -m paper_2504_05346_amd.peak_probe               # prints one JSON object
+    python -m paper_2504_05346_amd.peak_probe --syrk-data   # adds: the Hessian kernel by operand data
 
-bench.py --measured-peaks adds the same object to its line.  The numbers put the roofline
-fractions (quoted against the data-sheet peaks) next to what the chip sustains.
+bench.py adds the first object to its line as `measured_peaks`.  The numbers put the roofline
+fractions (quoted against the data-sheet peaks) next to what the chip sustains.  `--syrk-data`
+times the library's own accumulate call (same kernel, same instruction stream, same traffic) on
+calibration matrices that differ only in their values: the difference is what the power limit
+takes.
 """
 from __future__ import annotations
 
@@ -52,7 +56,54 @@ def measure(torch, mfma_ms: float = 20.0) -> dict:
     return out
 
 
+def syrk_by_data(torch, b: int = 11008, tokens: int = 262144, reps: int = 3) -> list:
+    """thanos_hessian_accumulate on [tokens, b] fp16 matrices of different content."""
+    from .binding import thanos_hessian_accumulate
+    X = torch.empty((tokens, b), dtype=torch.float16, device="cuda")
+    H = torch.zeros((b, b), dtype=torch.float32, device="cuda")
+    chunk = 16384
+
+    def fill(kind):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(0)
+        if kind == "zeros":
+            X.zero_()
+        elif kind == "ones":
+            X.fill_(1.0)
+        elif kind == "column-constant":      # random across channels, the same for every token
+            X[:] = torch.randn((1, b), generator=g, device="cuda").half()
+        else:
+            for t0 in range(0, tokens, chunk):
+                n = min(chunk, tokens - t0)
+                if kind == "bernoulli{0,1}":
+                    X[t0:t0 + n] = torch.randint(0, 2, (n, b), generator=g, device="cuda").half()
+                else:                        # "normal"
+                    X[t0:t0 + n] = torch.randn((n, b), generator=g, device="cuda",
+                                               dtype=torch.float32).half()
+
+    out = []
+    for kind in ("normal", "zeros", "ones", "bernoulli{0,1}", "column-constant", "normal"):
+        fill(kind)
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            H.zero_()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            thanos_hessian_accumulate(H, X)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        out.append({"data": kind, "ms": best, "tflops": tokens * b * (b + 1) / best / 1e9})
+    return out
+
+
 if __name__ == "__main__":
+    import sys
     import torch
     assert torch.cuda.is_available(), "needs a GPU"
-    print(json.dumps(measure(torch)))
+    res = measure(torch)
+    if "--syrk-data" in sys.argv[1:]:
+        res["syrk_by_data"] = syrk_by_data(torch)
+    print(json.dumps(res))
