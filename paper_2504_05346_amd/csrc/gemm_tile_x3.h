@@ -188,6 +188,36 @@ __device__ __forceinline__ void slab_store_x3(char* smem, int buf, int operand,
   }
 }
 
+// Producer of a reduction of exactly four whole slabs (K = 128: the block updates of the sweep,
+// panel and narrow updates of the factorisation), whole aligned operand.  Two slabs are in
+// flight: the loads of slab it + 2 are requested as soon as the registers of slab it have gone
+// to LDS, so a load has two multiply phases to arrive in; with one slab ahead (the loop below)
+// the producers wait for memory in every slab, which is a third of so short a product.  Written
+// without a loop: across a loop edge the compiler waits for ALL outstanding loads.
+template <bool KMAJOR>
+__device__ __forceinline__ void x3_produce4(char* smem, int operand, const float* __restrict__ P,
+                                            int64_t ld, int ext, int kbeg, int u) {
+  SlabSrcX3 src;
+  slab_src_x3<KMAJOR>(src, P, ld, ext, kbeg, u);
+  SlabRegsX3 r0, r1;
+  slab_load_x3<KMAJOR, true>(r0, src, 0, 4 * kXK, P);
+  slab_load_x3<KMAJOR, true>(r1, src, 1, 3 * kXK, P);
+  slab_store_x3<KMAJOR, false>(smem, 0, operand, r0, u);
+  slab_load_x3<KMAJOR, true>(r0, src, 2, 2 * kXK, P);
+  __syncthreads();
+  __syncthreads();
+  slab_store_x3<KMAJOR, false>(smem, 0, operand, r1, u);
+  slab_load_x3<KMAJOR, true>(r1, src, 3, kXK, P);
+  __syncthreads();
+  __syncthreads();
+  slab_store_x3<KMAJOR, false>(smem, 0, operand, r0, u);
+  __syncthreads();
+  __syncthreads();
+  slab_store_x3<KMAJOR, false>(smem, 0, operand, r1, u);
+  __syncthreads();
+  __syncthreads();
+}
+
 // Producer loop of one operand: split and store slab `it`, request slab `it + 1`, then the two
 // barriers of the slab (the consumers run the same barrier sequence).
 template <bool KMAJOR, bool FAST, bool MASKED>
@@ -196,11 +226,12 @@ __device__ __forceinline__ void x3_produce(char* smem, int operand, const float*
                                            int u) {
   SlabSrcX3 src;
   slab_src_x3<KMAJOR>(src, P, ld, ext, kbeg, u);
+  const int klen = kend - kbeg;
   SlabRegsX3 r;
-  slab_load_x3<KMAJOR, FAST>(r, src, 0, kend - kbeg, P);
+  slab_load_x3<KMAJOR, FAST>(r, src, 0, klen, P);
   for (int it = 0; it < nslab; ++it) {
     slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r, u);
-    slab_load_x3<KMAJOR, FAST>(r, src, it + 1, kend - kbeg - (it + 1) * kXK, P);
+    slab_load_x3<KMAJOR, FAST>(r, src, it + 1, klen - (it + 1) * kXK, P);
     __syncthreads();  // slab it is in LDS
     __syncthreads();  // consumers are done with it
   }
@@ -229,13 +260,15 @@ __device__ __forceinline__ void gemm_tile_x3(TileAcc& acc, char* smem, const flo
     if (wave >= 6) {
       const bool fast = vec_b && (B_KMAJOR ? n_ext % 4 == 0 : (kend - kbeg) % 4 == 0);
       const bool whole = n_ext == 128 && !ktail;
-      if (fast && whole) x3_produce<B_KMAJOR, true, false>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
+      if (fast && whole && kend - kbeg == 4 * kXK) x3_produce4<B_KMAJOR>(smem, 1, B, ldb, n_ext, kbeg, u);
+      else if (fast && whole) x3_produce<B_KMAJOR, true, false>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
       else if (fast) x3_produce<B_KMAJOR, true, true>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
       else x3_produce<B_KMAJOR, false, false>(smem, 1, B, ldb, n_ext, kbeg, kend, nslab, u);
     } else {
       const bool fast = vec_a && (A_KMAJOR ? m_ext % 4 == 0 : (kend - kbeg) % 4 == 0);
       const bool whole = m_ext == 128 && !ktail;
-      if (fast && whole) x3_produce<A_KMAJOR, true, false>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
+      if (fast && whole && kend - kbeg == 4 * kXK) x3_produce4<A_KMAJOR>(smem, 0, A, lda, m_ext, kbeg, u);
+      else if (fast && whole) x3_produce<A_KMAJOR, true, false>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
       else if (fast) x3_produce<A_KMAJOR, true, true>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
       else x3_produce<A_KMAJOR, false, false>(smem, 0, A, lda, m_ext, kbeg, kend, nslab, u);
     }
