@@ -18,7 +18,8 @@ Prints ONE JSON line:
   * `rooflines`: one entry per phase (algorithmic flops and bytes / phase time);
   * `extra`: the second workload of the target, the same layer at 50 % unstructured sparsity,
     timed the same way in the same run (only when the default workload is run);
-  * `measured_peaks`: what this GPU sustains in a loop of nothing but fp16 MFMAs (smooth and
+  * `measured_peaks`: the accumulate kernel on an all-zero matrix of the same shape, and what this
+    GPU sustains in a loop of nothing but fp16 MFMAs (smooth and
     random operands, with the shader clock it runs at) and in a plain HBM copy;
   * `cpu_baseline`: the float64 oracle timed on a bounded sample on the host cores.
 """
@@ -335,6 +336,25 @@ def main():
                 if m["operands"] == "random" and m["run"] == "sustained"]
         if ceil:
             out["roofline"]["frac_of_measured_mfma_only_rate"] = out["roofline"]["achieved"] / ceil[0]
+        # the accumulate call of this workload once more on an all-zero calibration matrix of the
+        # same shape: same kernel, instructions, addresses and traffic, operands that do not
+        # toggle.  What it gains over the timed rate is what the power limit takes on real data.
+        Xz = torch.zeros_like(X)
+        Hz = torch.zeros((args.b, args.b), dtype=torch.float32, device="cuda")
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            th.thanos_hessian_accumulate(Hz, Xz)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        del Xz, Hz
+        tf = args.tokens * args.b * (args.b + 1) / best / 1e9
+        mp["accumulate_same_kernel_on_zeros"] = {
+            "ms": best, "tflops": tf, "frac_of_peak": tf / out["roofline"]["peak"],
+            "note": "one call over all tokens; compare roofline.achieved (same kernel on the workload's data)"}
     if not (args.no_cpu_baseline or args.phases_only):
         out["cpu_baseline"] = cpu_baseline(args, W, X, torch)
     print(json.dumps(out))
