@@ -38,13 +38,13 @@ def _sym64(H):
     return np.tril(Hl) + np.tril(Hl, -1).T
 
 
-def _prune(W, H, mode, block, p=0.5, n=0, m=0):
+def _prune(W, H, mode, block, p=0.5, n=0, m=0, alpha=0.0):
     import torch
     import paper_2504_05346_amd as th
     c, b = W.shape
     tau = torch.full(((b + block - 1) // block,), -2.0, dtype=torch.float32, device="cuda")
     o = th.PruneOpts(mode=th.THANOS_NM if mode == "nm" else th.THANOS_UNSTRUCTURED, sparsity=p,
-                     n=n, m=m, block_size=block, damping=DAMP)
+                     n=n, m=m, block_size=block, damping=DAMP, outlier_fraction=alpha)
     if mode != "nm":
         o.threshold_out = tau.data_ptr()
     ws = torch.empty((th.thanos_prune_workspace_bytes(c, b, o),), dtype=torch.uint8, device="cuda")
@@ -108,6 +108,47 @@ def test_cfg4_5120_heavy_tailed_4of8(rho):
     check_nm_rows(W[rows.tolist()].cpu().numpy(), Hg, U,
                   Wo[rows.tolist()].cpu().numpy().astype(np.float64),
                   M[rows.tolist()].cpu().numpy(), 4, 8, 128, DAMP, f"cfg4 5120x5120 4:8 rho={rho}")
+
+
+def test_cfg4_5120_4of8_with_outlier_rows():
+    """The n:m algorithm with outlier rows (App. G.4.4, alpha = 0.1) at the size of configuration
+    4: the ceil(alpha c) rows of largest loss h_i = ||W_i X||^2 stay untouched, the others are
+    pruned 4:8 as before."""
+    c = b = 5120
+    alpha = 0.1
+    print(f"configuration 4: {c}x{b} 4:8 with {alpha} outlier rows", flush=True)
+    W, X, H = _device_layer(c, b, 0.7, outliers=True)
+    del X
+    Wo, M, _ = _prune(W, H, "nm", 128, n=4, m=8, alpha=alpha)
+    Hg = _sym64(H)
+    Wh = W.cpu().numpy()
+    Mg = M.cpu().numpy()
+    n_out = orc.num_outlier_rows(alpha, c)
+    kept_g = ~Mg.any(axis=1)                       # rows the GPU left alone
+    assert int(kept_g.sum()) == n_out == 512
+    # the same rows as the oracle's ranking of the row losses, unless the cut is a near-tie
+    h = orc.row_losses(Wh, Hg)
+    pruned_o = orc.pruned_rows(Wh, Hg, alpha)
+    hs = np.sort(h)
+    gap = (hs[c - n_out] - hs[c - n_out - 1]) / hs[c - n_out]
+    print(f"  row-loss gap at the cut {gap:.2e}", flush=True)
+    if gap > 1e-5:
+        np.testing.assert_array_equal(kept_g, ~pruned_o)
+    else:                                          # either side of a near-tie is acceptable
+        wrong = np.flatnonzero(kept_g != ~pruned_o)
+        assert len(wrong) <= 2 and np.all(np.abs(h[wrong] - hs[c - n_out]) <= 1e-5 * hs[c - n_out])
+    # untouched rows: bit-identical to the input, nothing masked
+    kept_idx = np.flatnonzero(kept_g)
+    np.testing.assert_array_equal(Wo[kept_idx.tolist()].cpu().numpy(),
+                                  Wh[kept_idx].astype(np.float32))
+    # pruned rows: 4 of every 8, exact zeros, sampled rows against the oracle
+    pr = np.flatnonzero(~kept_g)
+    assert bool((M[pr.tolist()].view(len(pr), b // 8, 8).sum(dim=2) == 4).all())
+    assert float(Wo[M == 1].abs().max()) == 0.0
+    U = orc.inverse_factor(orc.damped(Hg, DAMP))
+    rows = pr[sample_rows(len(pr), 48, seed=6)]
+    check_nm_rows(Wh[rows], Hg, U, Wo[rows.tolist()].cpu().numpy().astype(np.float64), Mg[rows],
+                  4, 8, 128, DAMP, "cfg4 5120x5120 4:8 alpha=0.1")
 
 
 @pytest.mark.parametrize("rho", [0.0, 0.7])

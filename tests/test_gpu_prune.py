@@ -255,7 +255,8 @@ def test_outlier_rows_argument_checks():
 
 # --------------------------------------------------------------------------- structured (Alg. 2)
 @pytest.mark.parametrize("c,b,p,alpha,dtype", [(200, 384, 0.5, 0.0, "f16"), (150, 300, 0.3, 0.1, "f32"),
-                                               (64, 1000, 0.25, 0.2, "f16")])
+                                               (64, 1000, 0.25, 0.2, "f16"),
+                                               (1536, 2048, 0.25, 0.05, "f16")])   # several tiles each way
 def test_structured(c, b, p, alpha, dtype):
     """Alg. 2: s = ceil(p b / (1 - alpha)) columns of smallest loss removed from the
     non-outlier rows in one shot."""
