@@ -5,7 +5,9 @@ tokens), GPU against the oracle:
   * configuration 4: 5120 x 5120, 4:8, heavy-tailed activations, B = 128 -- sampled rows;
   * configuration 5: 8192 x 8192, 60 % unstructured, B = 256, N(0, 0.015^2) weights, outlier
     channels -- sampled rows against the per-block thresholds the GPU reports.
-Each on the configured (independent) channels and on the correlated variant.
+Each on the configured (independent) channels and on the correlated variant.  Also the two
+"next" variants at a benchmark size: 4:8 with outlier rows (5120 x 5120) and structured pruning
+(Alg. 2, 4096 x 4096).
 """
 import types
 
@@ -167,3 +169,48 @@ def test_cfg5_8192_block256_60pct(rho):
                             Wo[rows.tolist()].cpu().numpy().astype(np.float64),
                             M[rows.tolist()].cpu().numpy(), tau, 0.6, 256, DAMP,
                             f"cfg5 8192x8192 60 % B=256 rho={rho}")
+
+
+def test_structured_4096_with_outlier_rows():
+    """Alg. 2 (structured pruning with outlier rows) on a 4096 x 4096 layer with 262144
+    calibration tokens: p = 0.3, alpha = 0.1, i.e. s = ceil(p b / (1 - alpha)) = 1366 columns
+    leave the 3686 rows of smallest loss, in one shot."""
+    import torch
+    import paper_2504_05346_amd as th
+    c = b = 4096
+    p, alpha = 0.3, 0.1
+    print(f"structured {c}x{b}, p={p}, alpha={alpha}", flush=True)
+    W, X, H = _device_layer(c, b, 0.7, seed=8)
+    del X
+    o = th.PruneOpts(mode=th.THANOS_STRUCTURED, sparsity=p, damping=DAMP, outlier_fraction=alpha)
+    ws = torch.empty((th.thanos_prune_workspace_bytes(c, b, o),), dtype=torch.uint8, device="cuda")
+    Wo = torch.empty((c, b), dtype=torch.float32, device="cuda")
+    M = torch.empty((c, b), dtype=torch.uint8, device="cuda")
+    info = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    th.thanos_prune_layer(W, H, o, Wo, None, M, ws, info)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    Hg = _sym64(H)
+    Wh = W.cpu().numpy()
+    Wg, Mg = Wo.cpu().numpy().astype(np.float64), M.cpu().numpy()
+    s_cols = orc.num_columns_to_remove(p, alpha, b)
+    n_out = orc.num_outlier_rows(alpha, c)
+    assert s_cols == 1366 and n_out == 410
+    # gaps of the oracle's two rankings at their cuts
+    rows_o = orc.pruned_rows(Wh, Hg, alpha)
+    hs = np.sort(orc.row_losses(Wh, Hg))
+    vs = np.sort(orc.column_losses(Wh.astype(np.float64), np.diag(Hg), rows_o))
+    gap_r = (hs[c - n_out] - hs[c - n_out - 1]) / hs[c - n_out]
+    gap_c = (vs[s_cols] - vs[s_cols - 1]) / vs[s_cols]
+    print(f"  gaps at the cuts: rows {gap_r:.2e}, columns {gap_c:.2e}", flush=True)
+    Wt, Mt = orc.prune_structured(Wh, Hg, p, alpha, DAMP)
+    assert int(Mg.sum()) == int(Mt.sum()) == s_cols * (c - n_out)
+    assert np.all(Wg[Mg == 1] == 0.0)
+    if not np.array_equal(Mg, Mt):
+        assert min(gap_r, gap_c) < 1e-5, "structured masks differ without a near-tie at a cut"
+        pytest.skip("near-tie at a cut of the structured ranking: W_hat not compared")
+    np.testing.assert_array_equal(Wg[~rows_o], Wh[~rows_o].astype(np.float64))
+    assert np.linalg.norm(Wg - Wt) <= 1e-3 * np.linalg.norm(Wt)
+    eo = orc.reconstruction_error(Wh, Wt, Hg)
+    eg = orc.reconstruction_error(Wh, Wg, Hg)
+    assert abs(eg - eo) <= 0.01 * eo
