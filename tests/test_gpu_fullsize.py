@@ -7,11 +7,11 @@ any size:
   * Hessian: sampled entries against float64 dot products of the same fp16 columns;
   * factor: U upper triangular, U^T (U (H_d e_j)) = e_j on sampled columns, and U against the
     oracle's own factor of the same matrix;
-  * 2:4 sweep (B = 128 and the paper's B = 512): exact pattern and zeros on the whole layer;
-    on >= 64 sampled rows (tile edges 127/128, 255/256, 2047/2048, first, last) every group
+  * 2:4 sweep (B = 128, the paper's B = 512, and 1024 / 2048 / 4096 of its block-size ablation):
+    exact pattern and zeros on the whole layer; on >= 64 sampled rows (16 for B >= 2048) (tile edges 127/128, 255/256, 2047/2048, first, last) every group
     decision against the oracle's decision on the weights that block saw, W_hat per row, the
     reconstruction error per row (tests/fullsize_util.py);
-  * unstructured sweep: exact count and zeros on the whole layer, the first block's mask against
+  * unstructured sweep (B = 128, 512, 2048): exact count and zeros on the whole layer, the first block's mask against
     a float32 partition of the full metric (ties included) and its threshold bit for bit; on the
     sampled rows every decision of EVERY block against the threshold the GPU reports for that
     block, W_hat and reconstruction error per row.
