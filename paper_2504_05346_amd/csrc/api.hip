@@ -14,7 +14,10 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
                     const float* H, const float* U, const float* xnorm2,
                     const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
                     void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
-                    PhaseTimer* pt, const float* Lfac, int64_t ldL);
+                    PhaseTimer* pt, const float* Lfac, int64_t ldL, bool prepared);
+thanos_status sweep_prepare(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                            const float* H, const thanos_prune_opts* o, long long n_out, float* W,
+                            void* ws);
 size_t structured_workspace_bytes(int64_t c, int64_t b);
 thanos_status structured(hipStream_t st, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
                          const float* H, float damping, long long s_cols, long long n_out,
@@ -349,13 +352,30 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
   const float* xn2 = opts->xnorm2_in;
   const float* Lfac = nullptr;  // lower factor of the index-reversed damped Hessian (this call's)
   int64_t ldL = 0;
+  const long long r_total =
+      (opts->mode == THANOS_UNSTRUCTURED) ? num_to_remove(opts->sparsity, c, b) : 0;
+  const long long n_out = num_outlier_rows(opts->outlier_fraction, c);
+  bool prepared = false;
+  // The working copy of the weights and the ranking of the row losses need nothing from the
+  // factorisation: with a factor to compute they run beside it on a helper stream (the chain
+  // of diagonal blocks leaves most of the chip idle) and are joined before the sweep.
+  AuxStream prep(s, (!U && !single_stream) ? 2 : 0, single_stream);
+  if (!prep.ok) return THANOS_ERR_HIP;
   if (!U) {
     float* Uw = reinterpret_cast<float*>(p);
     p += align_up((size_t)b * b * sizeof(float), 256);
     float* xw = reinterpret_cast<float*>(p);
     p += align_up((size_t)b * sizeof(float), 256);
+    if (!single_stream) {
+      THANOS_CHECK(prep.fork(0));
+      thanos_status sp = sweep_prepare(prep.stream, W_in, wdt, c, b, H, opts, n_out, W_out, sweep_ws);
+      if (sp != THANOS_OK) return sp;
+      THANOS_CHECK(prep.record(1));
+      prepared = true;
+    }
     thanos_status st = factor(s, H, b, opts->damping, Uw, xw, p, info_dev, single_stream);
     if (st != THANOS_OK) return st;
+    if (prepared) THANOS_CHECK(prep.join(1));
     U = Uw;
     xn2 = xw;
     Lfac = factor_L(p, b, &ldL);
@@ -363,12 +383,9 @@ static thanos_status prune_with_workspace(const void* W_in, thanos_dtype wdt, in
     hipLaunchKernelGGL(k_zero_info, dim3(1), dim3(1), 0, s, info_dev);
     THANOS_LAUNCH_CHECK();
   }
-  const long long r_total =
-      (opts->mode == THANOS_UNSTRUCTURED) ? num_to_remove(opts->sparsity, c, b) : 0;
-  const long long n_out = num_outlier_rows(opts->outlier_fraction, c);
   phase_mark(pt, THANOS_PHASE_PREP);
   thanos_status st = sweep(s, W_in, wdt, c, b, H, U, xn2, opts, r_total, n_out, W_out, W_out_cast,
-                           mask_out, sweep_ws, info_dev, single_stream, pt, Lfac, ldL);
+                           mask_out, sweep_ws, info_dev, single_stream, pt, Lfac, ldL, prepared);
   if (pt) {
     const thanos_status tc = pt->collect(opts->phase_ms_out);
     if (st == THANOS_OK) st = tc;

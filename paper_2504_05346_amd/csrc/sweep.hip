@@ -2174,19 +2174,19 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
   }
 }
 
-thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
-                    const float* H, const float* U, const float* xnorm2,
-                    const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
-                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
-                    PhaseTimer* pt, const float* Lfac, int64_t ldL) {
+// The part of the sweep that needs neither the factor nor the diagonal of H: the fp32 working
+// copy of the weights and, with outlier rows, the rows to leave alone.  The caller may run it on
+// another stream while the factorisation is going (the two touch disjoint memory) and then
+// passes prepared = true to sweep().
+thanos_status sweep_prepare(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                            const float* H, const thanos_prune_opts* o, long long n_out, float* W,
+                            void* ws) {
   const int B = o->block_size;
   const bool outliers = n_out > 0;
   const int smax_all = (o->mode == THANOS_NM && !o->mask_in) ? B / o->m * o->n : B;
-  const bool comp = sweep_uses_complement(o, b) && Lfac != nullptr;
   SweepWs w = carve_ws(ws, c, b, B, outliers, smax_all, sweep_uses_complement(o, b));
   const int64_t n = c * b;
   const unsigned nblk = (unsigned)ceil_div(n, 256);
-
   if (wdt == THANOS_F32)
     hipLaunchKernelGGL(k_to_f32<float>, dim3(nblk), dim3(256), 0, s, (const float*)W_in, W, n);
   else if (wdt == THANOS_F16)
@@ -2195,12 +2195,32 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     hipLaunchKernelGGL(k_to_f32<__hip_bfloat16>, dim3(nblk), dim3(256), 0, s,
                        (const __hip_bfloat16*)W_in, W, n);
   THANOS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_sqrt, dim3((unsigned)ceil_div(b, 256)), dim3(256), 0, s, xnorm2, w.sx, b);
-  THANOS_LAUNCH_CHECK();
   if (outliers) {
     thanos_status st = row_outliers(s, W, H, c, b, n_out, w.Hf, w.T, w.h, w.row_skip);
     if (st != THANOS_OK) return st;
   }
+  return THANOS_OK;
+}
+
+thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c, int64_t b,
+                    const float* H, const float* U, const float* xnorm2,
+                    const thanos_prune_opts* o, long long r_total, long long n_out, float* W,
+                    void* W_cast, uint8_t* mask, void* ws, int32_t* info, bool single_stream,
+                    PhaseTimer* pt, const float* Lfac, int64_t ldL, bool prepared) {
+  const int B = o->block_size;
+  const bool outliers = n_out > 0;
+  const int smax_all = (o->mode == THANOS_NM && !o->mask_in) ? B / o->m * o->n : B;
+  const bool comp = sweep_uses_complement(o, b) && Lfac != nullptr;
+  SweepWs w = carve_ws(ws, c, b, B, outliers, smax_all, sweep_uses_complement(o, b));
+  const int64_t n = c * b;
+  const unsigned nblk = (unsigned)ceil_div(n, 256);
+
+  if (!prepared) {
+    thanos_status st = sweep_prepare(s, W_in, wdt, c, b, H, o, n_out, W, ws);
+    if (st != THANOS_OK) return st;
+  }
+  hipLaunchKernelGGL(k_sqrt, dim3((unsigned)ceil_div(b, 256)), dim3(256), 0, s, xnorm2, w.sx, b);
+  THANOS_LAUNCH_CHECK();
 
   const bool aligned_b = (b % 4 == 0) && (B % 4 == 0);
   const int pair_w = (aligned_b && reinterpret_cast<uintptr_t>(W) % 8 == 0 &&
