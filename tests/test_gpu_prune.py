@@ -552,3 +552,29 @@ def test_block128_rows_split_between_two_solvers(p):
     assert _rel(Wg, Wt) < 1e-3
     _, Mo = orc.prune_fast(W, H, mode="unstructured", p=p, B=128, damp=0.01)
     assert (Mg != Mo).mean() < 1e-3
+
+
+# --------------------------------------------------------------------------- conditioning
+@pytest.mark.parametrize("T,rho,damp,mode,B", [
+    (512, 0.7, 0.01, "nm", 128),              # fewer tokens than channels: H is rank deficient
+    (256, 0.9, 0.01, "unstructured", 128),    # rank 256 of 1024, strongly correlated channels
+    (4096, 0.95, 0.001, "unstructured", 256),  # small damping, condition number > 1e4
+    (4096, 0.7, 0.0001, "nm", 128),
+])
+def test_ill_conditioned_hessians(T, rho, damp, mode, B):
+    """Damping is all that keeps these Hessians positive definite (condition numbers of the
+    damped matrix 5e3 .. 4e4); the fp32 factor and solves must still give the oracle's W_hat."""
+    from tests.gpu_util import gpu_prune
+    c, b = 256, 1024
+    W, H32 = _layer(c, b, T, "f16", rho=rho, seed=5)
+    H = H32.astype(np.float64)
+    kw = dict(n=2, m=4) if mode == "nm" else dict(p=0.5)
+    print(f"ill-conditioned {mode} T={T} rho={rho} damping={damp} B={B}", flush=True)
+    Wg, Mg, info = gpu_prune(W, H32, mode=mode, B=B, damp=damp, **kw)
+    assert info == 0
+    Wt, _ = orc.prune_fast(W, H, mode=mode, B=B, damp=damp, mask_in=Mg, **kw)
+    assert np.all(Wg[Mg == 1] == 0.0)
+    assert _rel(Wg, Wt) < 1e-3
+    eo = orc.reconstruction_error(W, Wt, H)
+    eg = orc.reconstruction_error(W, Wg.astype(np.float64), H)
+    assert abs(eg - eo) <= 0.01 * eo
