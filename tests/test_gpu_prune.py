@@ -578,3 +578,36 @@ def test_ill_conditioned_hessians(T, rho, damp, mode, B):
     eo = orc.reconstruction_error(W, Wt, H)
     eg = orc.reconstruction_error(W, Wg.astype(np.float64), H)
     assert abs(eg - eo) <= 0.01 * eo
+
+
+@pytest.mark.parametrize("mode", ["unstructured", "nm"])
+def test_dead_input_channels(mode):
+    """Input channels that are zero in every calibration token: H_jj = 0, so the metric of their
+    weights is 0 and they go first (ties in (row, column) order); the damping alone keeps the
+    Hessian positive definite.  No special case anywhere: masks as the oracle's, W_hat within
+    the usual bound."""
+    from tests.gpu_util import gpu_prune
+    c, b, T, B = 96, 512, 2048, 128
+    spec = LayerSpec("t", c=c, b=b, tokens=T, dtype="f16", rho=0.7, k_mix=16, seed=12)
+    W, X = make_weight(spec), make_calibration(spec)
+    dead = np.array([0, 5, 6, 130, 255, 256, 300, 511])        # 5 and 6 share a group of four
+    X[:, dead] = 0
+    H32 = orc.hessian(X).astype(np.float32)
+    H = H32.astype(np.float64)
+    assert np.all(np.diag(H)[dead] == 0.0)
+    kw = dict(n=2, m=4) if mode == "nm" else dict(p=0.5)
+    Wg, Mg, info = gpu_prune(W, H32, mode=mode, B=B, **kw)
+    assert info == 0
+    assert Mg[:, dead].all()                                   # every weight of a dead channel goes
+    if mode == "nm":
+        assert np.all(Mg.reshape(c, b // 4, 4).sum(axis=2) == 2)
+        assert not Mg[:, [4, 7]].any()                         # the group 4..7 is used up by 5 and 6
+    else:
+        assert int(Mg.sum()) == c * b // 2
+    Wo, Mo = orc.prune_fast(W, H, mode=mode, B=B, damp=0.01, **kw)
+    ndiff = int((Mg != Mo).sum())
+    assert ndiff <= 4, ndiff                                   # near-ties only (none at the dead channels)
+    np.testing.assert_array_equal(Mg[:, dead], Mo[:, dead])
+    Wt, _ = orc.prune_fast(W, H, mode=mode, B=B, damp=0.01, mask_in=Mg, **kw)
+    assert np.all(Wg[Mg == 1] == 0.0)
+    assert _rel(Wg, Wt) < 1e-3
