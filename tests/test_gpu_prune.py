@@ -611,3 +611,36 @@ def test_dead_input_channels(mode):
     Wt, _ = orc.prune_fast(W, H, mode=mode, B=B, damp=0.01, mask_in=Mg, **kw)
     assert np.all(Wg[Mg == 1] == 0.0)
     assert _rel(Wg, Wt) < 1e-3
+
+
+# --------------------------------------------------------------------------- invariances
+@pytest.mark.parametrize("mode", ["unstructured", "nm"])
+def test_hessian_scale_does_not_matter(mode):
+    """The update u R_hat^{-1} R and the order of the metric are unchanged by H -> kappa H when
+    the damping is relative (Sec. 4.1 / 4.2: H enters as 2 X X^T, (2/d) sum or X X^T alike).
+    With kappa a power of four every intermediate scales exactly (the factor by the power of
+    two sqrt(kappa)), so the results are identical bit for bit."""
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(200, 640, 2560, "f16", rho=0.7, seed=21)
+    kw = dict(n=2, m=4) if mode == "nm" else dict(p=0.5)
+    W1, M1, i1 = gpu_prune(W, H32, mode=mode, B=128, **kw)
+    W2, M2, i2 = gpu_prune(W, (4.0 * H32).astype(np.float32), mode=mode, B=128, **kw)
+    W3, M3, i3 = gpu_prune(W, (0.0625 * H32).astype(np.float32), mode=mode, B=128, **kw)
+    assert i1 == i2 == i3 == 0
+    np.testing.assert_array_equal(M1, M2)
+    np.testing.assert_array_equal(W1, W2)
+    np.testing.assert_array_equal(M1, M3)
+    np.testing.assert_array_equal(W1, W3)
+
+
+def test_nm_rows_are_independent():
+    """n:m: rows only meet in the shared inverse, so permuting the rows of W permutes the rows
+    of (W_hat, M) and changes nothing else (bit for bit: a row's arithmetic does not depend on
+    which tile or wavefront it lands in)."""
+    from tests.gpu_util import gpu_prune
+    W, H32 = _layer(300, 512, 2048, "f16", rho=0.7, seed=22)
+    perm = np.random.default_rng(0).permutation(W.shape[0])
+    W1, M1, _ = gpu_prune(W, H32, mode="nm", n=2, m=4, B=128)
+    W2, M2, _ = gpu_prune(np.ascontiguousarray(W[perm]), H32, mode="nm", n=2, m=4, B=128)
+    np.testing.assert_array_equal(M1[perm], M2)
+    np.testing.assert_array_equal(W1[perm], W2)
