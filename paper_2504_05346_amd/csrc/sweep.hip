@@ -1743,7 +1743,7 @@ struct UpdateArgs {
   int vec_w;            // W 8-byte and mask 2-byte aligned, b and col0 even: row pass in pairs
   // Unstructured mode: while the new weights are at hand, the columns right of the block are
   // histogrammed for the NEXT block's selection (window around the current threshold, see
-  // k_tie_rows / k_sel_start); hist == nullptr switches this off.
+  // k_select); hist == nullptr switches this off.
   unsigned int* hist;         // 2048 bins, global
   unsigned int* below_part;   // keys below the window, one count per workgroup
   unsigned int* cand_n;       // per workgroup: keys inside the window ...
@@ -1855,7 +1855,7 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
     }
   }
   if (a.hist == nullptr) return;
-  // one partial count of the keys below the window per workgroup (summed by k_sel_start:
+  // one partial count of the keys below the window per workgroup (summed by k_select:
   // thousands of atomics on one address would cost more than the pass), window bins by atomics
   for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
   if (lane == 0) nb_wave[wave] = nb;
