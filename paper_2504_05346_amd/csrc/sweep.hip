@@ -988,14 +988,34 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
     myrank[r] = s + __popcll(bal & ((1ull << lane) - 1ull));
     s += __popcll(bal);
   }
-  if (s > 32 * NTR && a.defer_large) {  // solved by the launch for larger systems
-    if (SEL == SEL_THRESHOLD && lane == 0) a.st_rw->deferred = 1;
-    return;
+  // A row with more unknowns than the tile grid holds (s > 32 NTR; rare): with the inverse K of
+  // the block's G at hand it is solved here through the complement, a system of bw - s < 32
+  // unknowns (see k_solve_tiled for the identity); without K it is left to the launch for
+  // larger systems.
+  bool comp = false;
+  if (s > 32 * NTR && a.defer_large) {
+    if (FULL || a.Kc == nullptr) {
+      if (SEL == SEL_THRESHOLD && lane == 0) a.st_rw->deferred = 1;
+      return;
+    }
+    comp = true;
+  }
+  const int ns = comp ? a.bw - s : s;  // unknowns of the system solved below
+  if (comp) {  // positions of the KEPT columns of the block
+    int before = 0;
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      const bool kept = col < a.bw && !sel[r];
+      const unsigned long long bal = __ballot(kept);
+      if (kept) sm.q[before + __popcll(bal & ((1ull << lane) - 1ull))] = (unsigned char)col;
+      before += __popcll(bal);
+    }
   }
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
     const int col = lane + 64 * r;
-    if (sel[r]) sm.q[myrank[r]] = (unsigned char)col;
+    if (sel[r] && !comp) sm.q[myrank[r]] = (unsigned char)col;
     if (col < a.bw) a.mask_out[i * a.b + a.j1 + col] = sel[r] ? 1 : 0;
   }
   if (SEL == SEL_THRESHOLD) {
@@ -1003,13 +1023,46 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   }
   float* lam_g = a.Lam + i * a.ldl;
   // s > 32 NTR (or, if FULL, anything but 32 NTR) cannot happen for a launch chosen by the host
-  if (s == 0 || s > 32 * NTR || (FULL && s != 32 * NTR)) {
+  if (s == 0 || (s > 32 * NTR && !comp) || (FULL && s != 32 * NTR)) {
 #pragma unroll
     for (int r = 0; r < CPL; ++r) {
       const int col = lane + 64 * r;
       if (col < a.bw) lam_g[col] = 0.f;
     }
     return;
+  }
+  // y[r] = sum_a x[a] K[a][lane + 64 r] for this wavefront (x in LDS, zeros skipped)
+  auto matvec_k = [&](const float* x, float (&y)[CPL]) {
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) y[r] = 0.f;
+    for (int aa = 0; aa < a.bw; ++aa) {
+      const float xa = x[aa];
+      if (xa == 0.f) continue;
+      const float* kr = a.Kc + (int64_t)aa * a.ldk;
+#pragma unroll
+      for (int r = 0; r < CPL; ++r) {
+        const int col = lane + 64 * r;
+        if (col < a.bw) y[r] = fmaf(xa, kr[col], y[r]);
+      }
+    }
+  };
+  if (comp) {
+    // right-hand side (w~ K)_k: w~ = the row's weights on the removed columns, zero elsewhere
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) sm.key[lane + 64 * r] = sel[r] ? wv[r] : 0.f;
+    WAVE_SYNC();
+    float t[CPL];
+    matvec_k(sm.key, t);
+    if (ns == 0) {  // the whole block goes: lambda = w~ K
+#pragma unroll
+      for (int r = 0; r < CPL; ++r) {
+        const int col = lane + 64 * r;
+        if (col < a.bw) lam_g[col] = t[r];
+      }
+      return;
+    }
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) sm.wrow[lane + 64 * r] = t[r];  // gathered below through q
   }
   WAVE_SYNC();
 
@@ -1018,17 +1071,17 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
   //      unknown m - pad.  A pivot costs one MFMA per live tile, most in the first tile row
   //      (NTR (NTR + 1) / 2 of them): with the short tile row in front, a system of 66 unknowns
   //      costs 2 * 6 + 32 * 3 + 32 MFMAs instead of 32 * 6 + 32 * 3 + 2. ----
-  const int nt = FULL ? NTR : (s + 31) >> 5;
-  const int pad = FULL ? 0 : 32 * nt - s;
-  auto valid = [&](int m) { return FULL || m < 32 - pad || (m >= 32 && m - pad < s); };
+  const int nt = FULL ? NTR : (ns + 31) >> 5;
+  const int pad = FULL ? 0 : 32 * nt - ns;
+  auto valid = [&](int m) { return FULL || m < 32 - pad || (m >= 32 && m - pad < ns); };
   auto unk = [&](int m) {  // clamped: always a valid index
-    return FULL ? m : min(m < 32 ? m : m - pad, s - 1);
+    return FULL ? m : min(m < 32 ? m : m - pad, ns - 1);
   };
 
   // ---- gather R_hat = G[q, q] into the tiles (all loads unconditional from clamped, valid
   //      indices, masked afterwards); right-hand side distributed by row ----
-  const float* G = a.P + a.j1 * a.b + a.j1;
-  const unsigned int bb = (unsigned int)a.b;  // q * b < 2^31
+  const float* G = comp ? a.Kc : a.P + a.j1 * a.b + a.j1;  // R_hat = G[q, q], or K[k, k]
+  const unsigned int bb = comp ? (unsigned int)a.ldk : (unsigned int)a.b;  // q * b < 2^31
   f32x16 T[NTR][NTR];
   unsigned int qcol[NTR];
 #pragma unroll
@@ -1182,6 +1235,21 @@ __global__ __launch_bounds__(64 * WPB, 2) void k_solve_mfma(SolveArgs a) {
     if (64 * z + lane < 32 * nt && valid(mrow(64 * z + lane)))
       sm.wrow[sm.q[unk(mrow(64 * z + lane))]] = zz[z];
   WAVE_SYNC();
+  if (comp) {
+    // wrow holds y on the kept columns: lambda = ((w~ - y~) K)_q
+#pragma unroll
+    for (int r = 0; r < CPL; ++r)
+      sm.key[lane + 64 * r] = (sel[r] ? wv[r] : 0.f) - sm.wrow[lane + 64 * r];
+    WAVE_SYNC();
+    float l[CPL];
+    matvec_k(sm.key, l);
+#pragma unroll
+    for (int r = 0; r < CPL; ++r) {
+      const int col = lane + 64 * r;
+      if (col < a.bw) lam_g[col] = sel[r] ? l[r] : 0.f;
+    }
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < CPL; ++r) {
     const int col = lane + 64 * r;
@@ -2008,9 +2076,13 @@ static void launch_update(hipStream_t s, UpdateArgs ua, dim3 tiles) {
 // at most half of every group never need it.
 bool sweep_uses_complement(const thanos_prune_opts* o, int64_t b) {
   const int B = o->block_size;
-  if (o->factor_in || B <= 128 || B % 4 != 0 || b % 4 != 0) return false;
+  if (o->factor_in) return false;
   if (o->mode == THANOS_NM && !o->mask_in && 2 * o->n <= o->m) return false;
-  return true;
+  // blocks of up to 128 columns: the one-wavefront solver holds 96 unknowns and takes the rare
+  // rows with more through the complement (no alignment needed there); nothing to do when no
+  // row can have more
+  if (B <= 128) return B > 96 && (o->mode != THANOS_NM || o->mask_in);
+  return B % 4 == 0 && b % 4 == 0;
 }
 
 size_t sweep_workspace_bytes(int64_t c, int64_t b, int B, bool outliers, int smax, bool comp) {
@@ -2099,8 +2171,8 @@ __global__ void k_init_state(SelState* st, long long r) {
 
 template <int SEL>
 static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
-  if (a.bw <= 128) a.Kc = nullptr;  // only the tiled solver knows the complement form
-  if (a.Kc) smax = SEL == SEL_NM ? std::min(smax, a.bw - smax) : a.bw / 2;  // unknowns per row
+  // tiled solver: rows that lose more than half of the block are solved through the complement
+  if (a.Kc && a.bw > 128) smax = SEL == SEL_NM ? std::min(smax, a.bw - smax) : a.bw / 2;
   if (a.bw <= 128 && smax <= 64) {
     constexpr int kWpb = 4;
     const size_t smem = kWpb * sizeof(SolveMfmaSmem<2>);
@@ -2128,7 +2200,9 @@ static void launch_solve(hipStream_t s, SolveArgs a, int smax) {
       hipLaunchKernelGGL((k_solve_mfma<SEL, kWpb, 3>), dim3((unsigned)ceil_div(a.c, kWpb)),
                          dim3(64 * kWpb), smem, s, a);
       a.defer_large = 0;
-      if (!(varies && a.bw > 96)) return;
+      // rows with more than 96 unknowns: solved by that launch through the complement when the
+      // blocks' K are at hand, else by the 128-thread kernel
+      if (!(varies && a.bw > 96) || a.Kc) return;
       a.s_min = 97;
     }
     hipLaunchKernelGGL((k_solve_wide<SEL, 128>), dim3((unsigned)a.c), dim3(128), 0, s, a);
@@ -2334,7 +2408,7 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
     sa.defer_large = 0;
     sa.tile_scratch = w.tile_scratch;
     sa.slot_floats = big_slot_floats(smax_all);
-    sa.Kc = (comp && bw > 128) ? w.Kc + blk * (int64_t)B * B : nullptr;
+    sa.Kc = comp ? w.Kc + blk * (int64_t)B * B : nullptr;
     sa.ldk = B;
     if (o->mask_in) {
       launch_solve<SEL_GIVEN>(s, sa, bw);
