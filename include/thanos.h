@@ -17,7 +17,8 @@
  *     enqueued asynchronously and the call returns without waiting for the device; results are
  *     ordered after the call on `stream`.  thanos_factor and thanos_prune_layer run part of
  *     their work on helper streams (default priority; two for the factorisation, one for the
- *     sweep), forked from and joined back into `stream` with events.  These host-side HIP
+ *     sweep, one for the part of the sweep's preparation that can run beside the
+ *     factorisation), forked from and joined back into `stream` with events.  These host-side HIP
  *     objects are the only state the library keeps: a call borrows them from a per-process pool
  *     (created on first use per device, one set per concurrently running call, never destroyed,
  *     because destroying a stream waits for it to drain).  On an error return every helper
