@@ -24,6 +24,7 @@
 // every barrier stalled the whole unit.  After the call only wavefronts 0..3 hold the result.
 #pragma once
 #include "gemm_tile.h"
+#include "timeline.h"
 
 namespace thanos {
 
@@ -230,8 +231,10 @@ __device__ __forceinline__ void x3_produce(char* smem, int operand, const float*
   SlabRegsX3 r;
   slab_load_x3<KMAJOR, FAST>(r, src, 0, klen, P);
   for (int it = 0; it < nslab; ++it) {
+    if (operand == 0 && u < 64) TL_MARK(8 + 4 * it);
     slab_store_x3<KMAJOR, MASKED>(smem, 0, operand, r, u);
     slab_load_x3<KMAJOR, FAST>(r, src, it + 1, klen - (it + 1) * kXK, P);
+    if (operand == 0 && u < 64) TL_MARK(8 + 4 * it + 1);
     __syncthreads();  // slab it is in LDS
     __syncthreads();  // consumers are done with it
   }
@@ -306,7 +309,9 @@ __device__ __forceinline__ void gemm_tile_x3(TileAcc& acc, char* smem, const flo
     };
     for (int it = 0; it < nslab; ++it) {
       __syncthreads();  // slab it is in LDS
+      if (wave == 0) TL_MARK(8 + 4 * it + 2);
       compute(0);
+      if (wave == 0) TL_MARK(8 + 4 * it + 3);
       __syncthreads();  // done with it
     }
   }

@@ -1826,6 +1826,7 @@ constexpr size_t kUpdSmemBytes = kXSmemBytes + 2048 * sizeof(unsigned int) +
 
 __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   extern __shared__ __attribute__((aligned(16))) char sm[];
+  if (threadIdx.x == 0) TL_MARK(0);
   unsigned int* hw = reinterpret_cast<unsigned int*>(sm + kXSmemBytes);  // window histogram
   unsigned int* nb_wave = hw + 2048;  // 8 counts per wavefront, then: staged keys, list offset
   uint2* stage = reinterpret_cast<uint2*>(nb_wave + 16);
@@ -1859,7 +1860,9 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
   TileAcc acc;
   acc_zero(acc);
   gemm_tile_x3<false, true>(acc, sm, A, a.ldl, m_ext, Bm, a.b, n_ext, 0, a.K, a.vec_a, a.vec_b);
+  if (threadIdx.x == 0) TL_MARK(1);
   const float* T = x3_stage_tile(acc, sm);
+  if (threadIdx.x == 0) TL_MARK(2);
   // row pass: wavefront w takes rows w, w + 8, ..., lane l the columns 2l, 2l + 1
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c0 = 2 * lane;
@@ -1895,6 +1898,8 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
       old[i] = *reinterpret_cast<const float2*>(Wg + off);
       mk[i] = in_block ? *reinterpret_cast<const unsigned short*>(Mg + off) : (unsigned short)0;
     }
+    TL_WAIT_LOADS();
+    if (threadIdx.x == 0) TL_MARK(3);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int row = wave + 8 * i;
@@ -1922,7 +1927,11 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
       }
     }
   }
-  if (a.hist == nullptr) return;
+  if (threadIdx.x == 0) TL_MARK(4);
+  if (a.hist == nullptr) {
+    if (threadIdx.x == 0) TL_MARK(5);
+    return;
+  }
   // one partial count of the keys below the window per workgroup (summed by k_select:
   // thousands of atomics on one address would cost more than the pass), window bins by atomics
   for (int off = 32; off > 0; off >>= 1) nb += __shfl_down(nb, off, 64);
@@ -1945,12 +1954,16 @@ __global__ __launch_bounds__(kXThreads, 4) void k_update(UpdateArgs a) {
     for (int e = threadIdx.x; e < 3 * 2048; e += kXThreads) a.hist[2048 + e] = 0u;
     if (threadIdx.x == 0) a.st->arrived = a.st->nbin = a.st->bar = 0u;
   }
-  if (!win) return;
+  if (!win) {
+    if (threadIdx.x == 0) TL_MARK(5);
+    return;
+  }
   const unsigned int n = min(nb_wave[8], (unsigned int)kCandStage);
   uint2* list = a.cand + (size_t)tile * kCandStage;
   for (unsigned int e = threadIdx.x; e < n; e += kXThreads) list[e] = stage[e];
   for (int e = threadIdx.x; e < 2048; e += kXThreads)
     if (hw[e]) atomicAdd(&a.hist[e], hw[e]);
+  if (threadIdx.x == 0) TL_MARK(5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2475,3 +2488,20 @@ thanos_status sweep(hipStream_t s, const void* W_in, thanos_dtype wdt, int64_t c
 }
 
 }  // namespace thanos
+
+#ifdef THANOS_TIMELINE
+// Diagnostic build only (see timeline.h): which launch to record, and the recorded timestamps.
+extern "C" int thanos_timeline_select(int grid_workgroups) {
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(thanos::g_timeline_grid), &grid_workgroups, sizeof(int));
+}
+extern "C" int thanos_timeline_read(unsigned long long* host, size_t bytes) {
+  if (bytes > sizeof(unsigned long long) * thanos::kTlWgs * thanos::kTlSlots) return -1;
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(thanos::g_timeline), bytes);
+}
+extern "C" int thanos_timeline_clear(void) {
+  void* p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(thanos::g_timeline)) != hipSuccess) return -1;
+  return (int)hipMemset(p, 0, sizeof(unsigned long long) * thanos::kTlWgs * thanos::kTlSlots);
+}
+#endif
+
