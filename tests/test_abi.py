@@ -32,6 +32,19 @@ def test_exports_every_declared_symbol(L):
         assert hasattr(L, n), n
 
 
+def test_diagnostic_builds_export_their_entry_points(L):
+    """libthanos_timeline.so is the same library with timestamps compiled in (timeline_probe.py);
+    the product library must not carry its entry points."""
+    here = os.path.dirname(L._name)
+    T = ctypes.CDLL(os.path.join(here, "libthanos_timeline.so"))
+    for n in _declared_functions() + ["thanos_timeline_select", "thanos_timeline_read",
+                                      "thanos_timeline_clear"]:
+        assert hasattr(T, n), n
+    assert not hasattr(L, "thanos_timeline_select")
+    P = ctypes.CDLL(os.path.join(here, "libthanos_probe.so"))
+    assert hasattr(P, "thanos_probe_mfma_f16") and hasattr(P, "thanos_probe_copy")
+
+
 def test_status_strings(L):
     import paper_2504_05346_amd as t
     seen = {t.thanos_status_string(s) for s in range(7)}
